@@ -1,0 +1,146 @@
+// Internal declarations shared by the HIP kernels and the host-side planner.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/subnetact.h"
+
+namespace sna {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+
+enum KClass {
+  KC_IGEMM = 0,      // sliced implicit-GEMM conv / linear on bf16 MFMA
+  KC_DIRECT = 1,     // direct conv (stems, fp32 tiny net)
+  KC_DEPTHWISE = 2,
+  KC_POOL = 3,       // max pool, global average pool
+  KC_SE = 4,         // squeeze-excite gate + channel scale
+  KC_LAYERNORM = 5,
+  KC_ATTENTION = 6,
+  KC_COPY = 7,       // request gather / logits scatter
+  KC_FOLD = 8,       // SubnetNorm statistics folding (load time)
+  KC_COUNT = 9
+};
+
+// ---- one problem of a grouped launch -------------------------------------------------------
+// A grouped launch carries up to SNA_MAX_GROUPS problems by value in the kernel
+// arguments; block b belongs to the problem whose [tile_start, tile_start + tiles)
+// range holds b.  One problem = one layer of one subnet cfg over that cfg's requests.
+
+struct ConvProblem {
+  const void* x;        // [N][H][W][C] activations (active channels, dense)
+  const void* w;        // max-size weights, already offset to the centre window's first tap
+  const float* scale;   // [K] or nullptr (= 1)
+  const float* shift;   // [K] or nullptr (= 0)
+  const void* res;      // [N][Ho][Wo][K] residual or nullptr
+  void* y;              // [N][Ho][Wo][K]
+  int N, H, W, C;       // C = active input channels
+  int Ho, Wo, K;        // K = active output channels
+  int R, S, stride, pad;
+  int wk, wr, ws;       // element strides of the stored weight tensor (c stride = 1)
+  int M;                // N*Ho*Wo
+  int C8, K8;           // C/8, R*S*C/8 (igemm only)
+  unsigned magic_c8;    // ceil(2^24 / C8)
+  int tiles_n;          // tiles along K (igemm)
+  int tile_start, tiles;
+  int act;              // sna_act
+  int out_fp32;         // 1: y is float (logits), else storage dtype
+  int y_stride;         // elements between output rows (>= K); lets a linear write a column block
+  int res_stride;
+  int res_after_act;    // 0: y = act(norm(conv) + res); 1: y = act(norm(conv)) + res
+};
+
+struct ConvGroupArgs {
+  int n;
+  ConvProblem p[SNA_MAX_GROUPS];
+};
+
+struct PoolProblem {    // max pool 3x3/2 or global average pool
+  const void* x; void* y;
+  int N, H, W, C, Ho, Wo;
+  int tile_start, tiles;
+};
+struct PoolGroupArgs { int n; PoolProblem p[SNA_MAX_GROUPS]; };
+
+struct DwProblem {
+  const void* x; const void* w; const float* scale; const float* shift; void* y;
+  int N, H, W, C, Ho, Wo;
+  int k, stride, pad;
+  int wr, ws;           // element strides of the stored [R][S][C_max] kernel
+  int act;
+  int tile_start, tiles;
+};
+struct DwGroupArgs { int n; DwProblem p[SNA_MAX_GROUPS]; };
+
+struct SeProblem {
+  const void* x;        // [N][HW][C] depthwise output
+  void* y;              // gated output (may alias x)
+  const void* w1; const float* b1;  // [Q_max][C_max] stored; leading [Q][C] used
+  const void* w2; const float* b2;  // [C_max][Q_max]
+  float* pooled;        // [N][C] scratch
+  float* gate;          // [N][C] scratch
+  int N, HW, C, Q;
+  int w1_stride, w2_stride;
+  int tile_start, tiles;
+};
+struct SeGroupArgs { int n; SeProblem p[SNA_MAX_GROUPS]; };
+
+struct LnProblem {
+  const void* x; const float* gamma; const float* beta; void* y;
+  int rows, cols;
+  int tile_start, tiles;
+};
+struct LnGroupArgs { int n; LnProblem p[SNA_MAX_GROUPS]; };
+
+struct AttnProblem {
+  const void* q; const void* k; const void* v; void* o;   // [B][S][heads*64], row stride ld
+  int B, S, heads, ld;
+  int tile_start, tiles;
+};
+struct AttnGroupArgs { int n; AttnProblem p[SNA_MAX_GROUPS]; };
+
+struct CopyItem { unsigned long src, dst; unsigned long n; };   // byte offsets / length (even)
+#define SNA_COPY_ITEMS 128
+struct CopyArgs { const void* src; void* dst; int n; CopyItem it[SNA_COPY_ITEMS]; };
+
+// ---- launchers (defined in the .hip files) ---------------------------------------------------
+hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s);
+void igemm_tile_shape(int variant, int* bm, int* bn);
+int igemm_num_variants();
+hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);
+hipError_t launch_maxpool(const PoolGroupArgs& a, int dtype, hipStream_t s);
+hipError_t launch_gap(const PoolGroupArgs& a, int dtype, hipStream_t s);
+hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s);
+hipError_t launch_se(const SeGroupArgs& a, hipStream_t s);
+hipError_t launch_layernorm(const LnGroupArgs& a, hipStream_t s);
+hipError_t launch_attention(const AttnGroupArgs& a, hipStream_t s);
+hipError_t launch_copy(const CopyArgs& a, hipStream_t s);
+hipError_t launch_fold_stats(const float* stats, float* folded, int n_subnets, long row_len, hipStream_t s);
+
+// ---- device helpers ---------------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+// round-to-nearest-even; inputs are finite
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == SNA_ACT_RELU) return fmaxf(v, 0.f);
+  if (act == SNA_ACT_HSWISH) return v * fminf(fmaxf(v + 3.f, 0.f), 6.f) * (1.f / 6.f);
+  if (act == SNA_ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
+  return v;
+}
+// problem lookup for a grouped launch: linear scan over <= 16 entries (uniform per block)
+template <class Args>
+__device__ __forceinline__ int find_problem(const Args& a, int b) {
+  int g = 0;
+#pragma unroll 1
+  for (int i = 1; i < a.n; ++i)
+    if (b >= a.p[i].tile_start) g = i;
+  return g;
+}
+#endif
+
+}  // namespace sna

@@ -1,0 +1,656 @@
+// C ABI and the host-side planner: validates the control tuples, groups requests by cfg, walks
+// the SuperNet in layer order and issues one grouped launch per layer slot.  LayerSelect is
+// decided here: a block beyond a cfg's depth produces no problem, hence no launch and no copy.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <functional>
+
+#include "host.h"
+
+namespace sna {
+const char* last_error_text();
+
+static inline int out_size(int h, int k, int stride) { return (h + 2 * (k / 2) - k) / stride + 1; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------------------------
+// cfg validation
+// ------------------------------------------------------------------------------------------
+static sna_status check_ch(int v, int mx, const char* what, int s, int j) {
+  if (v < 8 || v > mx) return fail(SNA_E_CFG_RANGE, "%s[%d][%d]=%d outside [8, %d]", what, s, j, v, mx);
+  if (v % 8) return fail(SNA_E_CFG_ALIGN, "%s[%d][%d]=%d is not a multiple of 8", what, s, j, v);
+  return SNA_OK;
+}
+
+static sna_status validate_cfg(const sna_supernet* net, const sna_subnet_cfg& c) {
+  const sna_arch_desc& a = net->T.arch;
+  if (c.subnet_id < 0 || c.subnet_id >= net->n_subnets)
+    return fail(SNA_E_SUBNET_ID, "subnet_id %d outside [0, %d)", c.subnet_id, net->n_subnets);
+  sna_status st;
+  if (a.family == SNA_FAMILY_TRANSFORMER) {
+    if (c.n_stages != 1) return fail(SNA_E_CFG_RANGE, "n_stages %d != 1", c.n_stages);
+    if (c.depth[0] < 1 || c.depth[0] > a.max_layers) return fail(SNA_E_CFG_RANGE, "depth %d", c.depth[0]);
+    if (c.in_h != a.seq_len) return fail(SNA_E_CFG_RANGE, "tokens %d != seq_len %d", c.in_h, a.seq_len);
+    for (int j = 0; j < c.depth[0]; ++j) {
+      const int at = c.block_mid_ch[0][j], ff = c.block_aux_ch[0][j];
+      if (at < a.head_dim || at > a.n_heads * a.head_dim || at % a.head_dim)
+        return fail(SNA_E_CFG_RANGE, "layer %d attention width %d", j, at);
+      if ((st = check_ch(ff, a.ffn, "ffn", 0, j)) != SNA_OK) return st;
+    }
+    return SNA_OK;
+  }
+  if (c.n_stages != a.n_stages) return fail(SNA_E_CFG_RANGE, "n_stages %d != %d", c.n_stages, a.n_stages);
+  if (c.in_h < 8 || c.in_h > a.max_res || c.in_w < 8 || c.in_w > a.max_res)
+    return fail(SNA_E_CFG_RANGE, "resolution %dx%d outside [8, %d]", c.in_h, c.in_w, a.max_res);
+  if ((st = check_ch(c.stage_out_ch[0], a.stem_ch, "stem", 0, 0)) != SNA_OK) return st;
+  if (a.family == SNA_FAMILY_MBV3 && c.stage_out_ch[0] != a.stem_ch)
+    return fail(SNA_E_CFG_RANGE, "MBV3 stem width is fixed at %d", a.stem_ch);
+  if (a.family == SNA_FAMILY_TINY && c.stage_out_ch[0] != a.stem_ch)
+    return fail(SNA_E_CFG_RANGE, "TINY stem width is fixed at %d", a.stem_ch);
+  for (int s = 0; s < a.n_stages; ++s) {
+    if (c.depth[s] < 1 || c.depth[s] > a.stage_max_depth[s])
+      return fail(SNA_E_CFG_RANGE, "depth[%d]=%d outside [1, %d]", s, c.depth[s], a.stage_max_depth[s]);
+    if ((st = check_ch(c.stage_out_ch[1 + s], a.stage_ch[s], "stage_out_ch", s, 0)) != SNA_OK) return st;
+    if (a.family == SNA_FAMILY_MBV3 && c.stage_out_ch[1 + s] != a.stage_ch[s])
+      return fail(SNA_E_CFG_RANGE, "MBV3 stage widths are fixed");
+    if (a.family == SNA_FAMILY_TINY) continue;
+    for (int j = 0; j < c.depth[s]; ++j) {
+      if ((st = check_ch(c.block_mid_ch[s][j], a.block_max_mid[s][j], "block_mid_ch", s, j)) != SNA_OK) return st;
+      if (a.family == SNA_FAMILY_MBV3) {
+        const int k = c.block_kernel[s][j];
+        if (k != 3 && k != 5 && k != 7) return fail(SNA_E_CFG_RANGE, "block_kernel[%d][%d]=%d", s, j, k);
+        if (a.stage_se[s] &&
+            (st = check_ch(c.block_aux_ch[s][j], a.block_max_aux[s][j], "block_aux_ch", s, j)) != SNA_OK)
+          return st;
+      }
+    }
+  }
+  return SNA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// one forward call
+// ------------------------------------------------------------------------------------------
+struct Fwd {
+  sna_supernet* net;
+  hipStream_t stream;
+  std::vector<Group> groups;
+  hipError_t err = hipSuccess;
+  int64_t macs = 0;
+  int launches = 0;
+
+  const ArchTables& T() const { return net->T; }
+  int esz() const { return net->T.esz; }
+
+  const sna_tensor_info& tensor(const std::string& name) const { return T().tensors[T().tidx.at(name)]; }
+  const char* wptr(const sna_tensor_info& ti) const { return net->weights + ti.offset; }
+  const float* scale_of(const std::string& norm, int subnet) const {
+    const sna_norm_info& ni = T().norms[T().nidx.at(norm)];
+    return net->folded + (size_t)subnet * 2 * T().row_len + ni.offset;
+  }
+  const float* shift_of(const std::string& norm, int subnet) const { return scale_of(norm, subnet) + T().row_len; }
+
+  // ---- profiling brackets ------------------------------------------------------------------
+  hipEvent_t next_event() {
+    if (net->ev_used == net->ev_pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      net->ev_pool.push_back(e);
+    }
+    return net->ev_pool[net->ev_used++];
+  }
+  template <class F>
+  void launch(int kc, double flops, double bytes, F&& f) {
+    if (err != hipSuccess) return;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (net->prof_on) {
+      a = next_event(); b = next_event();
+      if (a && b && hipEventRecord(a, stream) != hipSuccess) a = b = nullptr;
+    }
+    err = f();
+    if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
+      net->prof_recs.push_back({kc, a, b});
+      net->prof_flops[kc] += flops;
+      net->prof_bytes[kc] += bytes;
+      net->prof_launches[kc] += 1;
+    }
+    ++launches;
+  }
+
+  // ---- conv / linear ---------------------------------------------------------------------------
+  // Fill the WeightSlice part of a problem: leading K x C block, centre ksize window of the
+  // stored kernel, read at the stored tensor's strides.
+  void slice_conv(ConvProblem& p, const sna_tensor_info& ti, int K, int ksize, int stride) {
+    const int rmax = ti.kind == 0 ? ti.dims[1] : 1, smax = ti.kind == 0 ? ti.dims[2] : 1;
+    const int cmax = ti.c_pad;
+    p.wk = rmax * smax * cmax; p.wr = smax * cmax; p.ws = cmax;
+    const int r0 = (rmax - ksize) / 2, s0 = (smax - ksize) / 2;
+    p.w = wptr(ti) + ((size_t)r0 * p.wr + (size_t)s0 * p.ws) * (ti.dtype == SNA_DTYPE_BF16 ? 2 : 4);
+    p.K = K; p.R = ksize; p.S = ksize; p.stride = stride; p.pad = ksize / 2;
+    p.Ho = out_size(p.H, ksize, stride); p.Wo = out_size(p.W, ksize, stride);
+    p.M = p.N * p.Ho * p.Wo;
+    p.C8 = p.C / 8; p.K8 = p.R * p.S * p.C8;
+    p.magic_c8 = p.C8 > 0 ? (unsigned)(((1u << 24) + p.C8 - 1) / p.C8) : 0;
+    p.y_stride = K; p.res_stride = K;
+  }
+
+  static int pick_variant(int M, int K) {
+    // variants: 0 128x128, 1 128x64, 2 128x96, 3 128x32, 4 64x64, 5 64x128, 6 32x128
+    if (M <= 32) return 6;
+    int bn;
+    if (K <= 32) bn = 32;
+    else if (K <= 64) bn = 64;
+    else if (K <= 96) bn = 96;
+    else if (K <= 128) bn = 128;
+    else {
+      const int cand[3] = {128, 96, 64};
+      int best = 128, waste = 1 << 30;
+      for (int c : cand) {
+        const int w = (K + c - 1) / c * c - K;
+        if (w < waste) { waste = w; best = c; }
+      }
+      bn = best;
+    }
+    const long tiles128 = (long)((M + 127) / 128) * ((K + bn - 1) / bn);
+    if (tiles128 < 256 && (bn == 64 || bn == 128)) return bn == 64 ? 4 : 5;
+    return bn == 128 ? 0 : (bn == 64 ? 1 : (bn == 96 ? 2 : 3));
+  }
+
+  void run_igemm(std::vector<ConvProblem>& ps) {
+    if (ps.empty()) return;
+    std::vector<int> var(ps.size());
+    for (size_t i = 0; i < ps.size(); ++i) var[i] = pick_variant(ps[i].M, ps[i].K);
+    for (int v = 0; v < igemm_num_variants(); ++v) {
+      ConvGroupArgs a;
+      a.n = 0;
+      int bm, bn, start = 0;
+      igemm_tile_shape(v, &bm, &bn);
+      double flops = 0, bytes = 0;
+      for (size_t i = 0; i < ps.size(); ++i) {
+        if (var[i] != v) continue;
+        ConvProblem& p = ps[i];
+        p.tiles_n = (p.K + bn - 1) / bn;
+        p.tiles = ((p.M + bm - 1) / bm) * p.tiles_n;
+        p.tile_start = start;
+        start += p.tiles;
+        a.p[a.n++] = p;
+        const double mac = (double)p.M * p.K * p.C * p.R * p.S;
+        macs += (int64_t)mac;
+        flops += 2 * mac;
+        bytes += 2.0 * ((double)p.N * p.H * p.W * p.C + (double)p.K * p.R * p.S * p.C) +
+                 (p.out_fp32 ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K + (p.res ? 2.0 * p.M * p.K : 0.0);
+      }
+      if (a.n) launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, stream); });
+    }
+  }
+
+  void run_direct(std::vector<ConvProblem>& ps) {
+    if (ps.empty()) return;
+    ConvGroupArgs a;
+    a.n = 0;
+    int start = 0;
+    double flops = 0, bytes = 0;
+    for (ConvProblem& p : ps) {
+      p.tiles_n = (p.K + 15) / 16;
+      p.tiles = ((p.M + 255) / 256) * p.tiles_n;
+      p.tile_start = start;
+      start += p.tiles;
+      a.p[a.n++] = p;
+      const double mac = (double)p.M * p.K * p.C * p.R * p.S;
+      macs += (int64_t)mac;
+      flops += 2 * mac;
+      bytes += (double)esz() * ((double)p.N * p.H * p.W * p.C + (double)p.K * p.R * p.S * p.C) +
+               (p.out_fp32 ? 4.0 : (double)esz()) * (double)p.M * p.K + 8.0 * p.K +
+               (p.res ? (double)esz() * p.M * p.K : 0.0);
+    }
+    launch(KC_DIRECT, flops, bytes, [&] { return launch_direct_conv(a, T().arch.dtype, stream); });
+  }
+
+  // One conv slot over all groups.  `fill` returns false for groups that skip the slot.
+  void conv_slot(bool direct, const std::function<bool(Group&, ConvProblem&)>& fill) {
+    std::vector<ConvProblem> ps;
+    for (Group& g : groups) {
+      ConvProblem p;
+      memset(&p, 0, sizeof(p));
+      if (fill(g, p)) ps.push_back(p);
+    }
+    if (direct) run_direct(ps); else run_igemm(ps);
+  }
+
+  void pool_slot(bool is_max, const std::function<bool(Group&, PoolProblem&)>& fill) {
+    PoolGroupArgs a;
+    a.n = 0;
+    int start = 0;
+    double bytes = 0;
+    for (Group& g : groups) {
+      PoolProblem p;
+      memset(&p, 0, sizeof(p));
+      if (!fill(g, p)) continue;
+      if (is_max) {
+        p.Ho = out_size(p.H, 3, 2); p.Wo = out_size(p.W, 3, 2);
+        const long total = (long)p.N * p.Ho * p.Wo * (p.C / 8);
+        p.tiles = (int)((total + 255) / 256);
+      } else {
+        p.Ho = p.Wo = 1;
+        p.tiles = p.N * ((p.C / 8 + 31) / 32);
+      }
+      p.tile_start = start;
+      start += p.tiles;
+      bytes += (double)esz() * ((double)p.N * p.H * p.W * p.C + (double)p.N * p.Ho * p.Wo * p.C);
+      a.p[a.n++] = p;
+    }
+    if (!a.n) return;
+    const int dt = T().arch.dtype;
+    if (is_max) launch(KC_POOL, 0, bytes, [&] { return launch_maxpool(a, dt, stream); });
+    else launch(KC_POOL, 0, bytes, [&] { return launch_gap(a, dt, stream); });
+  }
+
+  // ---- request gather / logits scatter -----------------------------------------------------
+  void copy_items(const void* src, void* dst, std::vector<CopyItem>& items) {
+    for (size_t i = 0; i < items.size(); i += SNA_COPY_ITEMS) {
+      CopyArgs a;
+      a.src = src; a.dst = dst;
+      a.n = (int)std::min<size_t>(SNA_COPY_ITEMS, items.size() - i);
+      double bytes = 0;
+      for (int j = 0; j < a.n; ++j) { a.it[j] = items[i + j]; bytes += 2.0 * items[i + j].n; }
+      launch(KC_COPY, 0, bytes, [&] { return launch_copy(a, stream); });
+    }
+  }
+
+  sna_status run_tiny(const void* inputs, float* logits);
+  sna_status run_resnet(const void* inputs, float* logits);
+  sna_status run_mbv3(const void* inputs, float* logits);
+  sna_status run_transformer(const void* inputs, float* logits, void* hidden);
+
+  // Point every group at its requests' inputs: in place when they are contiguous in the call,
+  // otherwise gathered into the group's input buffer.
+  void bind_inputs(const void* inputs, const std::vector<size_t>& req_off, const std::vector<size_t>& req_bytes) {
+    std::vector<CopyItem> items;
+    for (Group& g : groups) {
+      if (g.contiguous) {
+        g.cur = (const char*)inputs + req_off[g.reqs[0]];
+      } else {
+        size_t d = 0;
+        for (int r : g.reqs) {
+          items.push_back({req_off[r], (size_t)(g.inbuf - net->arena) + d, req_bytes[r]});
+          d += req_bytes[r];
+        }
+        g.cur = g.inbuf;
+      }
+    }
+    if (!items.empty()) copy_items(inputs, net->arena, items);
+  }
+
+  // The head writes logits straight to the caller's buffer for contiguous groups, else into
+  // the group's scratch; scatter_logits() then moves rows to request order.
+  float* logits_target(Group& g, float* logits) {
+    const int nc = T().arch.n_classes;
+    return g.contiguous ? logits + (size_t)g.reqs[0] * nc : g.small;
+  }
+  void scatter_logits(float* logits) {
+    const int nc = T().arch.n_classes;
+    for (Group& g : groups) {
+      if (g.contiguous) continue;
+      std::vector<CopyItem> items;
+      for (int i = 0; i < g.n; ++i)
+        items.push_back({(size_t)i * nc * 4, (size_t)g.reqs[i] * nc * 4, (size_t)nc * 4});
+      copy_items(g.small, logits, items);
+    }
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// TINY: stem 3x3 -> SN -> ReLU; blocks conv3x3 -> SN -> ReLU (+ residual for j >= 1); GAP; linear
+// ------------------------------------------------------------------------------------------
+sna_status Fwd::run_tiny(const void*, float* logits) {
+  const sna_arch_desc& a = T().arch;
+  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = a.in_ch; }
+  auto conv = [&](const std::string& wname, const std::string& nname, int stride, bool residual,
+                  const std::function<bool(const Group&)>& active, const std::function<int(const Group&)>& kout) {
+    conv_slot(true, [&](Group& g, ConvProblem& p) {
+      if (!active(g)) return false;
+      p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+      slice_conv(p, tensor(wname), kout(g), 3, stride);
+      p.scale = scale_of(nname, g.cfg->subnet_id); p.shift = shift_of(nname, g.cfg->subnet_id);
+      p.act = SNA_ACT_RELU;
+      const int dst = g.cur_buf == 0 ? 1 : 0;
+      p.y = g.buf[dst];
+      if (residual) { p.res = g.cur; p.res_after_act = 1; }
+      g.cur = p.y; g.cur_buf = dst; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
+      return true;
+    });
+  };
+  conv("stem.w", "stem.sn", 1, false, [](const Group&) { return true; },
+       [&](const Group& g) { return g.cfg->stage_out_ch[0]; });
+  for (int s = 0; s < a.n_stages; ++s)
+    for (int j = 0; j < a.stage_max_depth[s]; ++j) {
+      const std::string p = "s" + std::to_string(s) + ".b" + std::to_string(j) + ".";
+      conv(p + "w", p + "sn", j == 0 ? 2 : 1, j > 0, [&](const Group& g) { return j < g.cfg->depth[s]; },
+           [&](const Group& g) { return g.cfg->stage_out_ch[1 + s]; });
+    }
+  pool_slot(false, [&](Group& g, PoolProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    p.y = g.buf[2];
+    g.cur = p.y; g.H = g.W = 1;
+    return true;
+  });
+  conv_slot(true, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = 1; p.W = 1; p.C = g.C;
+    slice_conv(p, tensor("head.w"), a.n_classes, 1, 1);
+    p.shift = (const float*)wptr(tensor("head.b"));
+    p.y = logits_target(g, logits); p.out_fp32 = 1;
+    return true;
+  });
+  scatter_logits(logits);
+  return SNA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// RESNET bottleneck SuperNet
+// ------------------------------------------------------------------------------------------
+sna_status Fwd::run_resnet(const void*, float* logits) {
+  const sna_arch_desc& a = T().arch;
+  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = a.in_ch; }
+  conv_slot(true, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    slice_conv(p, tensor("stem.w"), g.cfg->stage_out_ch[0], 7, 2);
+    p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
+    p.act = SNA_ACT_RELU; p.y = g.buf[0];
+    g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
+    return true;
+  });
+  pool_slot(true, [&](Group& g, PoolProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C; p.y = g.buf[1];
+    g.cur = p.y; g.cur_buf = 1; g.H = out_size(g.H, 3, 2); g.W = out_size(g.W, 3, 2);
+    return true;
+  });
+  // buffers: block input lives in buf[0] or buf[1]; buf[2] conv1 out, buf[3] conv2 out, buf[4] shortcut
+  for (int s = 0; s < a.n_stages; ++s)
+    for (int j = 0; j < a.stage_max_depth[s]; ++j) {
+      const std::string pre = "s" + std::to_string(s) + ".b" + std::to_string(j) + ".";
+      const int st = j == 0 ? a.stage_stride[s] : 1;
+      auto on = [&](const Group& g) { return j < g.cfg->depth[s]; };
+      conv_slot(false, [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+        slice_conv(p, tensor(pre + "conv1.w"), g.cfg->block_mid_ch[s][j], 1, 1);
+        p.scale = scale_of(pre + "sn1", g.cfg->subnet_id); p.shift = shift_of(pre + "sn1", g.cfg->subnet_id);
+        p.act = SNA_ACT_RELU; p.y = g.buf[2];
+        return true;
+      });
+      conv_slot(false, [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        const int m = g.cfg->block_mid_ch[s][j];
+        p.x = g.buf[2]; p.N = g.n; p.H = g.H; p.W = g.W; p.C = m;
+        slice_conv(p, tensor(pre + "conv2.w"), m, 3, st);
+        p.scale = scale_of(pre + "sn2", g.cfg->subnet_id); p.shift = shift_of(pre + "sn2", g.cfg->subnet_id);
+        p.act = SNA_ACT_RELU; p.y = g.buf[3];
+        return true;
+      });
+      if (j == 0)
+        conv_slot(false, [&](Group& g, ConvProblem& p) {
+          if (!on(g)) return false;
+          p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+          slice_conv(p, tensor(pre + "short.w"), g.cfg->stage_out_ch[1 + s], 1, st);
+          p.scale = scale_of(pre + "sn_short", g.cfg->subnet_id);
+          p.shift = shift_of(pre + "sn_short", g.cfg->subnet_id);
+          p.act = SNA_ACT_NONE; p.y = g.buf[4];
+          return true;
+        });
+      conv_slot(false, [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        const int m = g.cfg->block_mid_ch[s][j];
+        p.x = g.buf[3]; p.N = g.n; p.H = out_size(g.H, 3, st); p.W = out_size(g.W, 3, st); p.C = m;
+        slice_conv(p, tensor(pre + "conv3.w"), g.cfg->stage_out_ch[1 + s], 1, 1);
+        p.scale = scale_of(pre + "sn3", g.cfg->subnet_id); p.shift = shift_of(pre + "sn3", g.cfg->subnet_id);
+        p.act = SNA_ACT_RELU;
+        p.res = j == 0 ? (const void*)g.buf[4] : g.cur; p.res_after_act = 0;
+        const int dst = g.cur_buf == 0 ? 1 : 0;
+        p.y = g.buf[dst];
+        g.cur = p.y; g.cur_buf = dst; g.H = p.H; g.W = p.W; g.C = p.K;
+        return true;
+      });
+    }
+  pool_slot(false, [&](Group& g, PoolProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C; p.y = g.buf[2];
+    g.cur = p.y; g.H = g.W = 1;
+    return true;
+  });
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = 1; p.W = 1; p.C = g.C;
+    slice_conv(p, tensor("head.w"), a.n_classes, 1, 1);
+    p.shift = (const float*)wptr(tensor("head.b"));
+    p.y = logits_target(g, logits); p.out_fp32 = 1;
+    return true;
+  });
+  scatter_logits(logits);
+  return SNA_OK;
+}
+
+sna_status Fwd::run_mbv3(const void*, float*) { return fail(SNA_E_ARCH, "MBV3 forward is not built"); }
+sna_status Fwd::run_transformer(const void*, float*, void*) {
+  return fail(SNA_E_ARCH, "TRANSFORMER forward is not built");
+}
+
+static size_t folded_bytes(const ArchTables& T, int n_subnets) {
+  return align_up((size_t)n_subnets * 2 * T.row_len * sizeof(float) + 256, 256);
+}
+static size_t per_request_arena(const ArchTables& T) {
+  return (size_t)NBUF * align_up(T.per_image_elems * T.esz, 256) + align_up(T.in_elems_max * T.esz, 256) +
+         align_up(T.small_elems * 4, 256);
+}
+
+}  // namespace sna
+
+using namespace sna;
+
+extern "C" {
+
+const char* sna_last_error(void) { return last_error_text(); }
+
+int32_t sna_tensor_count(const sna_arch_desc* arch) {
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  return st != SNA_OK ? (int32_t)st : (int32_t)t.tensors.size();
+}
+int32_t sna_norm_count(const sna_arch_desc* arch) {
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  return st != SNA_OK ? (int32_t)st : (int32_t)t.norms.size();
+}
+sna_status sna_tensor_info_get(const sna_arch_desc* arch, int32_t index, sna_tensor_info* out) {
+  if (!out) return fail(SNA_E_NULL, "out is NULL");
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  if (st != SNA_OK) return st;
+  if (index < 0 || index >= (int)t.tensors.size()) return fail(SNA_E_ARCH, "tensor index %d", index);
+  *out = t.tensors[index];
+  return SNA_OK;
+}
+sna_status sna_norm_info_get(const sna_arch_desc* arch, int32_t index, sna_norm_info* out) {
+  if (!out) return fail(SNA_E_NULL, "out is NULL");
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  if (st != SNA_OK) return st;
+  if (index < 0 || index >= (int)t.norms.size()) return fail(SNA_E_ARCH, "norm index %d", index);
+  *out = t.norms[index];
+  return SNA_OK;
+}
+int64_t sna_weights_bytes(const sna_arch_desc* arch) {
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  return st != SNA_OK ? (int64_t)st : t.weight_bytes;
+}
+int64_t sna_stats_row_len(const sna_arch_desc* arch) {
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  return st != SNA_OK ? (int64_t)st : t.row_len;
+}
+int64_t sna_workspace_bytes(const sna_arch_desc* arch, int32_t n_subnets, int32_t max_batch) {
+  ArchTables t;
+  sna_status st = build_tables(arch, &t);
+  if (st != SNA_OK) return (int64_t)st;
+  if (n_subnets < 1 || max_batch < 1) return (int64_t)fail(SNA_E_BATCH, "n_subnets / max_batch < 1");
+  return (int64_t)(folded_bytes(t, n_subnets) + (size_t)max_batch * per_request_arena(t) +
+                   (size_t)SNA_MAX_GROUPS * 256 * (NBUF + 2));
+}
+
+sna_status sna_supernet_load(const sna_arch_desc* arch, const void* weights_dev, size_t weights_bytes,
+                             const void* stats_dev, size_t stats_bytes, int32_t n_subnets, int32_t max_batch,
+                             void* workspace_dev, size_t workspace_bytes, void* hip_stream, sna_supernet** out) {
+  if (!arch || !weights_dev || !workspace_dev || !out) return fail(SNA_E_NULL, "NULL argument");
+  *out = nullptr;
+  sna_supernet* net = new sna_supernet();
+  sna_status st = build_tables(arch, &net->T);
+  if (st != SNA_OK) { delete net; return st; }
+  if (n_subnets < 1 || max_batch < 1) { delete net; return fail(SNA_E_BATCH, "n_subnets / max_batch < 1"); }
+  if (net->T.row_len > 0 && !stats_dev) { delete net; return fail(SNA_E_NULL, "stats_dev is NULL"); }
+  if (weights_bytes < (size_t)net->T.weight_bytes) {
+    delete net;
+    return fail(SNA_E_WORKSPACE, "weights blob %zu B < %lld B", weights_bytes, (long long)net->T.weight_bytes);
+  }
+  if (stats_bytes < (size_t)n_subnets * 4 * net->T.row_len * sizeof(float)) {
+    delete net;
+    return fail(SNA_E_WORKSPACE, "statistics table too small");
+  }
+  const int64_t need = sna_workspace_bytes(arch, n_subnets, max_batch);
+  if ((int64_t)workspace_bytes < need) {
+    delete net;
+    return fail(SNA_E_WORKSPACE, "workspace %zu B < %lld B", workspace_bytes, (long long)need);
+  }
+  if (((uintptr_t)weights_dev | (uintptr_t)workspace_dev | (uintptr_t)stats_dev) & 255) {
+    delete net;
+    return fail(SNA_E_WORKSPACE, "buffers must be 256-byte aligned");
+  }
+  net->weights = (const char*)weights_dev;
+  net->stats = (const float*)stats_dev;
+  net->workspace = (char*)workspace_dev;
+  net->workspace_bytes = workspace_bytes;
+  net->folded = (float*)workspace_dev;
+  net->arena = net->workspace + folded_bytes(net->T, n_subnets);
+  net->arena_bytes = workspace_bytes - folded_bytes(net->T, n_subnets);
+  net->n_subnets = n_subnets;
+  net->max_batch = max_batch;
+  hipError_t e = launch_fold_stats(net->stats, net->folded, n_subnets, net->T.row_len, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { delete net; return fail(SNA_E_HIP, "fold_stats: %s", hipGetErrorString(e)); }
+  *out = net;
+  return SNA_OK;
+}
+
+void sna_supernet_free(sna_supernet* net) {
+  if (!net) return;
+  for (hipEvent_t e : net->ev_pool) (void)hipEventDestroy(e);
+  delete net;
+}
+
+sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs,
+                              const int32_t* req_cfg, int32_t n_requests, const void* inputs_dev,
+                              float* logits_dev, void* hidden_dev, void* hip_stream) {
+  if (!net || !cfgs || !req_cfg) return fail(SNA_E_NULL, "NULL argument");
+  if (n_requests < 0 || n_requests > net->max_batch)
+    return fail(SNA_E_BATCH, "n_requests %d outside [0, %d]", n_requests, net->max_batch);
+  if (n_cfgs < 1) return fail(SNA_E_BATCH, "n_cfgs < 1");
+  if (n_requests == 0) { net->last_macs = 0; net->last_launches = 0; return SNA_OK; }
+  if (!inputs_dev || !logits_dev) return fail(SNA_E_NULL, "NULL device buffer");
+  if (((uintptr_t)inputs_dev | (uintptr_t)logits_dev) & 3) return fail(SNA_E_WORKSPACE, "inputs / logits must be 4-byte aligned");
+  const ArchTables& T = net->T;
+  const sna_arch_desc& a = T.arch;
+
+  Fwd f;
+  f.net = net;
+  f.stream = (hipStream_t)hip_stream;
+  std::vector<int> gid(n_cfgs, -1);
+  std::vector<size_t> req_off(n_requests), req_bytes(n_requests);
+  size_t off = 0;
+  for (int r = 0; r < n_requests; ++r) {
+    const int ci = req_cfg[r];
+    if (ci < 0 || ci >= n_cfgs) return fail(SNA_E_BATCH, "req_cfg[%d]=%d outside [0, %d)", r, ci, n_cfgs);
+    if (gid[ci] < 0) {
+      sna_status st = validate_cfg(net, cfgs[ci]);
+      if (st != SNA_OK) return st;
+      if ((int)f.groups.size() == SNA_MAX_GROUPS) return fail(SNA_E_BATCH, "more than %d distinct cfgs in one call", SNA_MAX_GROUPS);
+      gid[ci] = (int)f.groups.size();
+      Group g;
+      g.cfg = &cfgs[ci];
+      g.cfg_index = ci;
+      f.groups.push_back(g);
+    }
+    Group& g = f.groups[gid[ci]];
+    if (g.n > 0 && g.reqs.back() != r - 1) g.contiguous = false;
+    g.reqs.push_back(r);
+    g.n++;
+    const sna_subnet_cfg& c = cfgs[ci];
+    const size_t elems = a.family == SNA_FAMILY_TRANSFORMER ? (size_t)c.in_h * a.hidden
+                                                            : (size_t)c.in_h * c.in_w * a.in_ch;
+    req_bytes[r] = elems * T.esz;
+    req_off[r] = off;
+    off += req_bytes[r];
+  }
+  // carve the arena: per group NBUF activation buffers, an input buffer and fp32 scratch
+  char* cur = net->arena;
+  const size_t act_b = align_up(T.per_image_elems * T.esz, 256);
+  const size_t in_b = align_up(T.in_elems_max * T.esz, 256), sm_b = align_up(T.small_elems * 4, 256);
+  for (Group& g : f.groups) {
+    for (int i = 0; i < NBUF; ++i) { g.buf[i] = cur; cur += align_up(act_b * g.n, 256); }
+    g.inbuf = cur; cur += align_up(in_b * g.n, 256);
+    g.small = (float*)cur; cur += align_up(sm_b * g.n, 256);
+  }
+  if ((size_t)(cur - net->arena) > net->arena_bytes) return fail(SNA_E_WORKSPACE, "arena overflow");
+
+  if (net->prof_on && net->prof_recs.size() > 200000) return fail(SNA_E_BATCH, "profile buffer full: call sna_profile_read");
+  f.bind_inputs(inputs_dev, req_off, req_bytes);
+  sna_status st;
+  switch (a.family) {
+    case SNA_FAMILY_TINY: st = f.run_tiny(inputs_dev, logits_dev); break;
+    case SNA_FAMILY_RESNET: st = f.run_resnet(inputs_dev, logits_dev); break;
+    case SNA_FAMILY_MBV3: st = f.run_mbv3(inputs_dev, logits_dev); break;
+    case SNA_FAMILY_TRANSFORMER: st = f.run_transformer(inputs_dev, logits_dev, hidden_dev); break;
+    default: st = fail(SNA_E_ARCH, "family");
+  }
+  if (st != SNA_OK) return st;
+  if (f.err != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(f.err));
+  net->last_macs = f.macs;
+  net->last_launches = f.launches;
+  return SNA_OK;
+}
+
+sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t* launches) {
+  if (!net) return fail(SNA_E_NULL, "net is NULL");
+  if (macs) *macs = net->last_macs;
+  if (launches) *launches = net->last_launches;
+  return SNA_OK;
+}
+
+static const char* kClassNames[SNA_N_KCLASS] = {"igemm_conv_linear", "direct_conv", "depthwise", "pool",
+                                                "squeeze_excite", "layernorm", "attention", "copy",
+                                                "fold_stats", "", "", ""};
+const char* sna_profile_class_name(int32_t k) { return (k >= 0 && k < SNA_N_KCLASS) ? kClassNames[k] : ""; }
+
+sna_status sna_profile_enable(sna_supernet* net, int32_t on) {
+  if (!net) return fail(SNA_E_NULL, "net is NULL");
+  net->prof_on = on != 0;
+  return SNA_OK;
+}
+
+sna_status sna_profile_read(sna_supernet* net, double ms[SNA_N_KCLASS], int64_t launches[SNA_N_KCLASS],
+                            double flops[SNA_N_KCLASS], double bytes[SNA_N_KCLASS]) {
+  if (!net || !ms || !launches || !flops || !bytes) return fail(SNA_E_NULL, "NULL argument");
+  for (int i = 0; i < SNA_N_KCLASS; ++i) ms[i] = 0;
+  for (const ProfRec& r : net->prof_recs) {
+    hipError_t e = hipEventSynchronize(r.b);
+    float t = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    if (e != hipSuccess) return fail(SNA_E_HIP, "event: %s", hipGetErrorString(e));
+    ms[r.kc] += t;
+  }
+  for (int i = 0; i < SNA_N_KCLASS; ++i) {
+    launches[i] = net->prof_launches[i]; flops[i] = net->prof_flops[i]; bytes[i] = net->prof_bytes[i];
+    net->prof_launches[i] = 0; net->prof_flops[i] = 0; net->prof_bytes[i] = 0;
+  }
+  net->prof_recs.clear();
+  net->ev_used = 0;
+  return SNA_OK;
+}
+
+}  // extern "C"

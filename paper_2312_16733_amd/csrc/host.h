@@ -1,0 +1,69 @@
+// Host-side state of a resident SuperNet and of one forward call.
+#pragma once
+#include <map>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace sna {
+
+constexpr int NBUF = 8;              // activation buffers per group in the arena
+constexpr float SN_EPS = 1e-5f;
+
+struct ArchTables {
+  sna_arch_desc arch;
+  std::vector<sna_tensor_info> tensors;
+  std::vector<sna_norm_info> norms;
+  std::map<std::string, int> tidx, nidx;
+  int64_t weight_bytes = 0;
+  int64_t row_len = 0;
+  int64_t per_image_elems = 0;       // largest activation of one request, in elements
+  int64_t in_elems_max = 0;          // largest request input, in elements
+  int64_t small_elems = 0;           // per-request fp32 scratch (pooled vectors, gates, logits)
+  int esz = 2;                       // bytes per stored activation / weight element
+};
+
+sna_status build_tables(const sna_arch_desc* arch, ArchTables* t);
+sna_status fail(sna_status st, const char* fmt, ...);
+
+struct ProfRec { int kc; hipEvent_t a, b; };
+
+struct Group {
+  const sna_subnet_cfg* cfg = nullptr;
+  int cfg_index = 0;
+  int n = 0;                         // requests routed to this cfg
+  std::vector<int> reqs;             // their positions in the call, ascending
+  bool contiguous = true;
+  char* buf[NBUF] = {nullptr};
+  char* inbuf = nullptr;
+  float* small = nullptr;
+  // running state of the activation handed from layer to layer
+  const void* cur = nullptr;
+  int H = 0, W = 0, C = 0;
+  int cur_buf = -1;
+};
+
+}  // namespace sna
+
+struct sna_supernet {
+  sna::ArchTables T;
+  const char* weights = nullptr;
+  const float* stats = nullptr;
+  char* workspace = nullptr;
+  size_t workspace_bytes = 0;
+  float* folded = nullptr;           // [n_subnets][2][row_len]
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  int n_subnets = 0, max_batch = 0;
+  // bookkeeping of the last forward
+  int64_t last_macs = 0;
+  int last_launches = 0;
+  // per-launch event timing
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+  std::vector<sna::ProfRec> prof_recs;
+  double prof_flops[SNA_N_KCLASS] = {0}, prof_bytes[SNA_N_KCLASS] = {0};
+  int64_t prof_launches[SNA_N_KCLASS] = {0};
+};

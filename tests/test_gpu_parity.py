@@ -1,0 +1,205 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (needs an MI355X)."""
+import copy
+import sys
+
+import numpy as np
+import pytest
+
+import synth
+from helpers import setup, check_parity, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def to_dev(torch, spec, x):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if spec.dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to("cuda:0")
+
+
+def run_single(torch, net, spec, cfg, x):
+    out = net.forward([cfg], np.zeros(len(x), np.int32), to_dev(torch, spec, x))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+# ------------------------------------------------------------------ cfg 1: tiny conv net, fp32
+def test_tiny_all_cfgs(torch_mod):
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.TinySpec()
+    W, S, C = setup(spec, 8)
+    net = sna.Supernet(spec, W, S, 8, 8)
+    worst = 0.0
+    for c in C:
+        x = synth.make_inputs(spec, 4, c.in_h, c.in_w, 7)
+        say("tiny cfg", c.subnet_id, c.depth, c.stage_out_ch)
+        got = run_single(torch, net, spec, c, x)
+        e, _ = check_parity(got, oracle.forward(spec, W, S, c, x), "fp32", f"tiny cfg {c.subnet_id}")
+        worst = max(worst, e)
+    say("tiny worst rel err", worst)
+    net.close()
+
+
+# ------------------------------------------------------------------ cfg 2: ResNet-shaped, bf16
+SMALL_RESNET = synth.ResNetSpec(n_classes=24, stem_ch=16, stage_ch=(32, 64, 96, 128),
+                                max_depth=(3, 3, 4, 3), res_choices=(40, 48, 57))
+
+
+def test_resnet_small_supernet_all_cfgs(torch_mod):
+    """Small supernet: odd resolutions, ragged tiles, every cfg, batch 3."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = SMALL_RESNET
+    W, S, C = setup(spec, 8)
+    net = sna.Supernet(spec, W, S, 8, 8)
+    for c in C:
+        x = synth.make_inputs(spec, 3, c.in_h, c.in_w, 7)
+        say("resnet-small cfg", c.subnet_id, c.depth, c.stage_out_ch, c.in_h)
+        got = run_single(torch, net, spec, c, x)
+        e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"small cfg {c.subnet_id}")
+        say("   rel err %.3e undecided %d" % (e, und))
+    net.close()
+
+
+@pytest.fixture(scope="module")
+def resnet_full(torch_mod):
+    import paper_2312_16733_amd as sna
+    spec = synth.ResNetSpec()
+    W, S, C = setup(spec, 16)
+    net = sna.Supernet(spec, W, S, 16, 64)
+    yield spec, W, S, C, net
+    net.close()
+
+
+@pytest.mark.parametrize("ci,batch", [(0, 1), (0, 16), (5, 2), (9, 1), (12, 3), (15, 1), (15, 2)])
+def test_resnet_full_supernet(torch_mod, resnet_full, ci, batch):
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    c = C[ci]
+    x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 11)
+    say("resnet cfg", ci, "batch", batch, "res", c.in_h, c.depth, c.stage_out_ch)
+    got = run_single(torch, net, spec, c, x)
+    e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"resnet cfg {ci} b{batch}")
+    say("   rel err %.3e undecided %d" % (e, und))
+
+
+def test_resnet_batch64_sampled(torch_mod, resnet_full):
+    """Full batch 64 in the benchmark's launch configuration; the oracle checks sampled requests
+    one by one (per-request results do not depend on batch mates)."""
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    for ci in (0, 7, 15):
+        c = C[ci]
+        x = synth.make_inputs(spec, 64, c.in_h, c.in_w, 12)
+        say("resnet b64 cfg", ci)
+        got = run_single(torch, net, spec, c, x)
+        assert np.all(np.isfinite(got))
+        for r in (0, 37, 63):
+            check_parity(got[r:r + 1], oracle.forward(spec, W, S, c, x[r:r + 1]), "bf16", f"b64 cfg {ci} req {r}")
+        # batch independence on the GPU itself: request 5 alone gives the same bits
+        alone = run_single(torch, net, spec, c, x[5:6])
+        np.testing.assert_array_equal(alone[0], got[5])
+
+
+# ------------------------------------------------------------------ cfg 4: mixed-subnet batch
+def test_mixed_batch_equals_single_subnet_runs(torch_mod, resnet_full):
+    import oracle
+    torch = torch_mod
+    spec, W, S, _, net = resnet_full
+    C = synth.enumerate_cfgs(spec, 16, 16733, fixed_res=224)
+    route = synth.zipf_assignment(64, 16, 4)
+    x = synth.make_inputs(spec, 64, 224, 224, 13)
+    say("mixed batch: groups", np.bincount(route, minlength=16).tolist())
+    got = net.forward(C, route, to_dev(torch, spec, x))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for ci in sorted(set(route.tolist())):
+        idx = np.nonzero(route == ci)[0]
+        single = run_single(torch, net, spec, C[ci], x[idx])
+        np.testing.assert_array_equal(got[idx], single, err_msg=f"cfg {ci}")
+    for r in (0, 21, 63):            # and against the oracle on sampled requests
+        check_parity(got[r:r + 1], oracle.forward(spec, W, S, C[route[r]], x[r:r + 1]), "bf16", f"mixed req {r}")
+
+
+def test_mixed_batch_mixed_resolutions_small(torch_mod):
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = SMALL_RESNET
+    W, S, C = setup(spec, 8)
+    net = sna.Supernet(spec, W, S, 8, 16)
+    route = np.array([3, 0, 3, 7, 1, 0, 7, 7, 5, 3, 0], dtype=np.int32)
+    xs = [synth.make_inputs(spec, 1, C[ci].in_h, C[ci].in_w, 100 + r) for r, ci in enumerate(route)]
+    flat = np.concatenate([a.ravel() for a in xs])
+    got = net.forward(C, route, to_dev(torch, spec, flat))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for r, ci in enumerate(route):
+        check_parity(got[r:r + 1], oracle.forward(spec, W, S, C[ci], xs[r]), "bf16", f"req {r} cfg {ci}")
+    net.close()
+
+
+# ------------------------------------------------------------------ operator behaviour on the GPU
+def test_gpu_subnetnorm_row_and_layerselect(torch_mod, resnet_full):
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    c = C[3]
+    x = synth.make_inputs(spec, 1, c.in_h, c.in_w, 14)
+    base = run_single(torch, net, spec, c, x)
+    wrong = copy.deepcopy(c); wrong.subnet_id = 4
+    assert rel_err(run_single(torch, net, spec, wrong, x), base).max() > 1e-2
+    deeper = copy.deepcopy(c)
+    s = next(i for i in range(4) if c.depth[i] < spec.max_depth[i])
+    deeper.block_mid_ch[s][deeper.depth[s]] = 64
+    deeper.depth[s] += 1
+    assert rel_err(run_single(torch, net, spec, deeper, x), base).max() > 1e-3
+    np.testing.assert_array_equal(run_single(torch, net, spec, c, x), base)     # deterministic
+
+
+def test_error_paths(torch_mod, resnet_full):
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    x = to_dev(torch, spec, synth.make_inputs(spec, 1, C[0].in_h, C[0].in_w, 15))
+    for field, val, status in [("subnet_id", 99, -5), ("in_h", 4000, -3)]:
+        bad = copy.deepcopy(C[0]); setattr(bad, field, val)
+        with pytest.raises(sna.SnaError) as ei:
+            net.forward([bad], [0], x)
+        assert ei.value.status == status
+    bad = copy.deepcopy(C[0]); bad.depth[1] = 9
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward([bad], [0], x)
+    assert ei.value.status == -3
+    bad = copy.deepcopy(C[0]); bad.block_mid_ch[0][0] = 36
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward([bad], [0], x)
+    assert ei.value.status == -4
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward([C[0]], [0] * 65, x)
+    assert ei.value.status == -6
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward([C[0]], [1], x)
+    assert ei.value.status == -6
+    out = net.forward([C[0]], [], x)                      # empty call: nothing to do
+    assert out.shape[0] == 0
+    got = net.forward([C[0]], [0], x)                     # handle still usable
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(got.cpu().numpy()))
