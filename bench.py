@@ -1,0 +1,163 @@
+"""Benchmark of the SubNetAct forward path on one MI355X.
+
+Workload (BASELINE config 2): the ResNet-50-shaped elastic SuperNet in bf16, 16 seeded subnet
+cfgs ordered smallest to largest, batch 64, synthetic inputs resident in HBM.  One step = one
+subnet_forward call over a batch of 64 requests of one cfg; consecutive steps walk the cfg list,
+so K steps sweep the subnet range K/16 times (and actuate a different subnet on every call).
+`value` = images/s over the timed K steps.  A separate, event-bracketed pass over the same steps
+gives the per-kernel-class durations for the roofline object; a third section reports images/s
+at batch 1 / 16 / 64 for the smallest, median and largest cfg.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(spec, W, S, C, seed):
+    """The oracle as it stands, on the host cores: one request through every cfg."""
+    import numpy as np
+
+    import oracle
+    import synth
+    cores = len(os.sched_getaffinity(0))
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    oracle.forward(spec, W, S, C[0], synth.make_inputs(spec, 1, C[0].in_h, C[0].in_w, seed))   # warm
+    per = 8
+    t0 = time.perf_counter()
+    n = 0
+    for c in C:
+        oracle.forward(spec, W, S, c, synth.make_inputs(spec, per, c.in_h, c.in_w, seed))
+        n += 1
+        if time.perf_counter() - t0 > 40:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": n * per / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"{per} requests through each of the first {n} of {len(C)} cfgs (smallest first), "
+                      f"oracle.forward bf16-storage mode, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; the path shards by request across "
+              "replicated workers and has no multi-GPU step to time (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2312_16733_amd as sna
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    spec = synth.ResNetSpec()
+    n_cfgs, B = 16, args.batch
+    W = synth.make_weights(spec, 2312)
+    S = synth.make_stats(spec, n_cfgs, 2312)
+    C = synth.enumerate_cfgs(spec, n_cfgs, 16733)
+    net = sna.Supernet(spec, W, S, n_cfgs, max(B, 64))
+    cfgs_c = [net.prepare_cfgs([c]) for c in C]
+    route = np.zeros(B, np.int32)
+    inputs = {}
+    for c in C:
+        if c.in_h not in inputs:
+            inputs[c.in_h] = torch.from_numpy(synth.make_inputs(spec, max(B, 64), c.in_h, c.in_w, 5)) \
+                .to(torch.bfloat16).to(dev)
+    logits = torch.empty((max(B, 64), spec.n_classes), dtype=torch.float32, device=dev)
+
+    def step(i, batch=B, r=route):
+        ci = i % n_cfgs
+        net.forward(cfgs_c[ci], r[:batch], inputs[C[ci].in_h], logits=logits)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    value = args.steps * B / dt
+
+    # event-bracketed pass over the same steps: per-class kernel time and algorithmic work
+    net.profile_enable(True)
+    macs_total = 0
+    for i in range(args.steps):
+        step(i)
+        macs_total += net.last_forward_info()[0]
+    torch.cuda.synchronize()
+    prof = net.profile_read()
+    net.profile_enable(False)
+    ig = prof.get("igemm_conv_linear", {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+    achieved = ig["flops"] / (ig["ms"] * 1e-3) / 1e12 if ig["ms"] > 0 else 0.0
+    classes = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] / args.steps,
+                   "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12 if v["ms"] > 0 else 0.0,
+                   "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0}
+               for k, v in prof.items()}
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "kernel": "igemm_kernel (all tile variants)",
+                "avg_launch_us": 1e3 * ig["ms"] / max(ig["launches"], 1),
+                "launches": ig["launches"],
+                "hbm_gbs_algorithmic": ig["bytes"] / (ig["ms"] * 1e-3) / 1e9 if ig["ms"] > 0 else 0.0,
+                "classes": classes}
+
+    detail = None
+    if not args.no_detail:
+        detail = {}
+        for b in (1, 16, 64):
+            for tag, ci in (("min", 0), ("median", n_cfgs // 2), ("max", n_cfgs - 1)):
+                for i in range(3):
+                    step(ci, b)
+                torch.cuda.synchronize()
+                reps = 20
+                t1 = time.perf_counter()
+                for i in range(reps):
+                    step(ci, b)
+                torch.cuda.synchronize()
+                d = (time.perf_counter() - t1) / reps
+                detail[f"b{b}_{tag}"] = {"images_per_s": b / d, "ms": d * 1e3,
+                                         "gmacs_per_image": synth.subnet_macs(spec, C[ci]) / 1e9}
+
+    out = {"metric": "subnet images/s at batch 64 across the subnet range", "value": value,
+           "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "ResNet-50-shaped elastic SuperNet (BASELINE config 2), bf16, "
+                                  f"batch {B}, 16 seeded subnet cfgs walked smallest to largest, one cfg per step",
+                      "batch": B, "n_cfgs": n_cfgs,
+                      "gmacs_per_image_range": [synth.subnet_macs(spec, C[0]) / 1e9,
+                                                synth.subnet_macs(spec, C[-1]) / 1e9],
+                      "mean_gmacs_per_image": macs_total / (args.steps * B) / 1e9},
+           "achieved_tflops_whole_step": 2.0 * macs_total / dt / 1e12,
+           "roofline": roofline}
+    if detail is not None:
+        out["detail"] = detail
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec, W, S, C, 5)
+    net.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

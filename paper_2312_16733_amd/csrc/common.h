@@ -52,6 +52,7 @@ struct ConvProblem {
 
 struct ConvGroupArgs {
   int n;
+  int total_tiles;      // sum of tiles over the problems
   ConvProblem p[SNA_MAX_GROUPS];
 };
 

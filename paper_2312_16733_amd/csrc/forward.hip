@@ -160,7 +160,14 @@ struct Fwd {
   void run_igemm(std::vector<ConvProblem>& ps) {
     if (ps.empty()) return;
     std::vector<int> var(ps.size());
-    for (size_t i = 0; i < ps.size(); ++i) var[i] = pick_variant(ps[i].M, ps[i].K);
+    for (size_t i = 0; i < ps.size(); ++i) {
+      const ConvProblem& q = ps[i];
+      if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 32) {
+        err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
+        return;
+      }
+      var[i] = pick_variant(q.M, q.K);
+    }
     for (int v = 0; v < igemm_num_variants(); ++v) {
       ConvGroupArgs a;
       a.n = 0;
@@ -181,6 +188,7 @@ struct Fwd {
         bytes += 2.0 * ((double)p.N * p.H * p.W * p.C + (double)p.K * p.R * p.S * p.C) +
                  (p.out_fp32 ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K + (p.res ? 2.0 * p.M * p.K : 0.0);
       }
+      a.total_tiles = start;
       if (a.n) launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, stream); });
     }
   }
@@ -204,6 +212,7 @@ struct Fwd {
                (p.out_fp32 ? 4.0 : (double)esz()) * (double)p.M * p.K + 8.0 * p.K +
                (p.res ? (double)esz() * p.M * p.K : 0.0);
     }
+    a.total_tiles = start;
     launch(KC_DIRECT, flops, bytes, [&] { return launch_direct_conv(a, T().arch.dtype, stream); });
   }
 
@@ -417,7 +426,7 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
     g.cur = p.y; g.H = g.W = 1;
     return true;
   });
-  conv_slot(false, [&](Group& g, ConvProblem& p) {
+  conv_slot(a.n_classes % 8 != 0, [&](Group& g, ConvProblem& p) {
     p.x = g.cur; p.N = g.n; p.H = 1; p.W = 1; p.C = g.C;
     slice_conv(p, tensor("head.w"), a.n_classes, 1, 1);
     p.shift = (const float*)wptr(tensor("head.b"));

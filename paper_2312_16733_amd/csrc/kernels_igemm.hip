@@ -6,14 +6,19 @@
 // The weight operand is the resident max-size tensor: a block reads the leading K_active rows,
 // and inside each (k, r, s) the leading C_active channels, through the tensor's own strides.
 // The reduction index is flattened over the ACTIVE extent only, in units of 8 channels
-// (16 bytes): unit u -> (r, s, c8) = (u / C8 / S, u / C8 % S, u % C8), so a narrow subnet pays
-// for its own K, not for the SuperNet's.  Active channel counts are multiples of 8, so a unit
-// never straddles a tap and every 16-byte load is aligned.
+// (16 bytes): unit u -> (tap rs, c8) = (u / C8, u % C8), so a narrow subnet pays for its own K,
+// not for the SuperNet's.  Active channel counts are multiples of 8, so a unit never straddles a
+// tap and every 16-byte load is aligned.
 //
-// Tiling: 256 threads = 4 waves; block tile BM x BN, K step 32, double-buffered LDS with the next
-// tile's global loads in flight during the MFMAs; v_mfma_f32_32x32x16_bf16, fp32 accumulators.
-// Epilogue (fused SubnetNorm scale/shift, residual, activation) runs on the accumulators.
-// A launch is grouped: each block finds its problem (one per subnet cfg) from the block index.
+// Tiling: 256 threads = 4 waves; block tile BM x BN, K step 64, double-buffered LDS (one barrier
+// per step) with the next step's global loads in flight during the MFMAs;
+// v_mfma_f32_32x32x16_bf16, fp32 accumulators.  Per-thread addressing is set up once: a base
+// offset and a tap-validity bitmask per fetched row, tap offsets in a small LDS table; the K loop
+// only adds.  The epilogue (fused SubnetNorm scale/shift, residual, activation) goes through a
+// per-wave fp32 LDS tile so that residual loads and output stores are 16 bytes per lane and
+// contiguous along channels.  Blocks are renumbered so that consecutive tiles (which share
+// activation rows) run on the same XCD and meet in its L2.
+// A launch is grouped: each block finds its problem (one per subnet cfg) from its tile number.
 #include "common.h"
 
 namespace sna {
@@ -21,104 +26,130 @@ namespace sna {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BK = 32;            // reduction elements per LDS stage
-constexpr int LDS_STRIDE = 40;    // bf16 per LDS row: 32 + 8 pad -> 80-byte rows, conflict-free b128 reads
+constexpr int BK = 64;             // reduction elements per LDS stage
+constexpr int LDS_STRIDE = 72;     // bf16 per LDS row: 64 + 8 pad -> 144-byte rows, conflict-free b128 reads
 constexpr int NTHREADS = 256;
+constexpr int TAP_TABLE = 40;      // entries per tap table (taps <= 32, rest zero)
+constexpr int SMEM_HEAD = 512;     // bytes reserved for the two tap tables
+
+template <int BM, int BN, int WARPS_M, int WARPS_N>
+struct IgemmCfg {
+  static constexpr int WTM = BM / WARPS_M, WTN = BN / WARPS_N;
+  static constexpr int TM = WTM / 32, TN = WTN / 32;
+  static constexpr int EPI_STRIDE = WTN + 4;                                 // floats per staged row
+  static constexpr int TILE_BYTES = 2 * (BM + BN) * LDS_STRIDE * 2;
+  static constexpr int EPI_BYTES = 4 * 32 * EPI_STRIDE * 4;
+  static constexpr int SMEM = SMEM_HEAD + (TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES);
+};
 
 template <int BM, int BN, int WARPS_M, int WARPS_N>
 __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs args) {
+  using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N>;
   static_assert(WARPS_M * WARPS_N == 4, "4 waves");
-  constexpr int WTM = BM / WARPS_M, WTN = BN / WARPS_N;
-  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
   static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-  constexpr int A_IT = (BM * 4 + NTHREADS - 1) / NTHREADS;
-  constexpr int B_IT = (BN * 4 + NTHREADS - 1) / NTHREADS;
+  constexpr int A_IT = BM / 32, B_IT = BN / 32;      // rows fetched per thread (32 rows per pass)
 
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (BM + BN) * LDS_STRIDE];
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int* tap_x = (int*)smem;
+  int* tap_w = tap_x + TAP_TABLE;
+  bf16_t* tiles = (bf16_t*)(smem + SMEM_HEAD);
 
-  const int g = find_problem(args, blockIdx.x);
+  // XCD-aware renumbering: hardware block b runs on XCD b % 8; give each XCD a contiguous tile range
+  const int per_xcd = gridDim.x >> 3;
+  const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile_id >= args.total_tiles) return;
+
+  const int g = find_problem(args, tile_id);
   const ConvProblem& p = args.p[g];
-  const int local = blockIdx.x - p.tile_start;
+  const int local = tile_id - p.tile_start;
   const int tn = local % p.tiles_n, tm = local / p.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WARPS_N, wn = wave % WARPS_N;
-  const int kc = tid & 3;                 // this thread's 16-byte unit inside a K step
-  const int lrow = tid >> 2;              // 0..63
+  const int kc = tid & 7;                 // this thread's 16-byte unit inside a K step
+  const int lrow = tid >> 3;              // 0..31
 
   const bf16_t* __restrict__ X = (const bf16_t*)p.x;
   const bf16_t* __restrict__ Wt = (const bf16_t*)p.w;
-  const int C = p.C, H = p.H, Wd = p.W, S = p.S;
+  const int C = p.C, H = p.H, Wd = p.W, S = p.S, RS = p.R * p.S;
 
-  // per-thread A rows: pixel coordinates of the rows this thread fetches
-  long a_base[A_IT];
-  int a_ih0[A_IT], a_iw0[A_IT];
+  if (tid < TAP_TABLE) {
+    int tx = 0, tw = 0;
+    if (tid < RS) {
+      const int r = tid / S, s = tid - r * S;
+      tx = (r * Wd + s) * C;
+      tw = r * p.wr + s * p.ws;
+    }
+    tap_x[tid] = tx;
+    tap_w[tid] = tw;
+  }
+
+  // rows this thread fetches: base offset of the window's first tap and which taps are in range
+  int a_base[A_IT];
+  unsigned a_mask[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
-    const int row = lrow + 64 * i;
-    const int m = m0 + row;
-    if (row < BM && m < p.M) {
+    const int m = m0 + lrow + 32 * i;
+    a_base[i] = 0;
+    a_mask[i] = 0;
+    if (m < p.M) {
       const int q = m % p.Wo, t = m / p.Wo;
       const int pp = t % p.Ho, n = t / p.Ho;
-      a_base[i] = (long)n * H * Wd * C;
-      a_ih0[i] = pp * p.stride - p.pad;
-      a_iw0[i] = q * p.stride - p.pad;
-    } else {
-      a_base[i] = 0;
-      a_ih0[i] = -100000;               // never in range -> zero fill
-      a_iw0[i] = 0;
+      const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
+      a_base[i] = ((n * H + ih0) * Wd + iw0) * C;
+      unsigned mk = 0;
+      for (int r = 0; r < p.R; ++r)
+        for (int s = 0; s < S; ++s)
+          if (ih0 + r >= 0 && ih0 + r < H && iw0 + s >= 0 && iw0 + s < Wd) mk |= 1u << (r * S + s);
+      a_mask[i] = mk;
     }
   }
-  long b_base[B_IT];
-  bool b_ok[B_IT];
+  int b_base[B_IT];
+  unsigned b_ok = 0;
 #pragma unroll
   for (int j = 0; j < B_IT; ++j) {
-    const int row = lrow + 64 * j;
-    const int k = n0 + row;
-    b_ok[j] = (row < BN) && (k < p.K);
-    b_base[j] = (long)k * p.wk;
+    const int k = n0 + lrow + 32 * j;
+    if (k < p.K) b_ok |= 1u << j;
+    b_base[j] = k * p.wk;
   }
 
-  uint4 a_reg[A_IT], b_reg[B_IT];
-  const int KT = (p.K8 + 3) >> 2;         // K steps of 32 elements
+  // reduction position of this thread's unit: tap rs and channel octet c8
+  int rs = kc / p.C8;
+  int c8 = kc - rs * p.C8;
 
-  auto fetch = [&](int kt) {
-    const int u = kt * 4 + kc;
-    const bool u_ok = u < p.K8;
-    const int rs = (int)(((unsigned long long)(unsigned)u * p.magic_c8) >> 24);
-    const int c8 = u - rs * p.C8;
-    const int r = rs / S, s = rs - r * S;
+  uint4 a_reg[A_IT], b_reg[B_IT];
+  const int KT = (p.K8 + 7) >> 3;         // K steps of 64 elements
+  __syncthreads();                        // tap tables visible
+
+  auto fetch = [&]() {
+    const bool u_ok = rs < RS;
+    const int rsc = u_ok ? rs : RS;       // entry RS of the tables is zero
+    const int tx = tap_x[rsc] + c8 * 8, tw = tap_w[rsc] + c8 * 8;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      const int ih = a_ih0[i] + r, iw = a_iw0[i] + s;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (u_ok && ih >= 0 && ih < H && iw >= 0 && iw < Wd)
-        v = *(const uint4*)(X + a_base[i] + ((long)ih * Wd + iw) * C + c8 * 8);
+      if (u_ok && ((a_mask[i] >> rs) & 1u)) v = *(const uint4*)(X + (a_base[i] + tx));
       a_reg[i] = v;
     }
-    const long woff = (long)r * p.wr + (long)s * p.ws + c8 * 8;
 #pragma unroll
     for (int j = 0; j < B_IT; ++j) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (u_ok && b_ok[j]) v = *(const uint4*)(Wt + b_base[j] + woff);
+      if (u_ok && ((b_ok >> j) & 1u)) v = *(const uint4*)(Wt + (b_base[j] + tw));
       b_reg[j] = v;
     }
+    c8 += 8;                              // advance one K step
+    while (c8 >= p.C8) { c8 -= p.C8; ++rs; }
   };
   auto stage = [&](int buf) {
-    bf16_t* As = lds + buf * (BM + BN) * LDS_STRIDE;
+    bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE;
     bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
-    for (int i = 0; i < A_IT; ++i) {
-      const int row = lrow + 64 * i;
-      if (row < BM) *(uint4*)(As + row * LDS_STRIDE + kc * 8) = a_reg[i];
-    }
+    for (int i = 0; i < A_IT; ++i) *(uint4*)(As + (lrow + 32 * i) * LDS_STRIDE + kc * 8) = a_reg[i];
 #pragma unroll
-    for (int j = 0; j < B_IT; ++j) {
-      const int row = lrow + 64 * j;
-      if (row < BN) *(uint4*)(Bs + row * LDS_STRIDE + kc * 8) = b_reg[j];
-    }
+    for (int j = 0; j < B_IT; ++j) *(uint4*)(Bs + (lrow + 32 * j) * LDS_STRIDE + kc * 8) = b_reg[j];
   };
 
   f32x16 acc[TM][TN];
@@ -129,14 +160,14 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs arg
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  fetch(0);
+  fetch();
   stage(0);
   __syncthreads();
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
   for (int kt = 0; kt < KT; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < KT) fetch(kt + 1);
-    const bf16_t* As = lds + buf * (BM + BN) * LDS_STRIDE;
+    if (kt + 1 < KT) fetch();
+    const bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE;
     const bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
@@ -157,43 +188,90 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs arg
     __syncthreads();
   }
 
-  // epilogue: accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+  // ---- epilogue -----------------------------------------------------------------------------
+  // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of a 32x32 tile.
+  // Per 32-row strip: SubnetNorm scale/shift on the accumulators, fp32 strip into this wave's LDS
+  // region, then each lane takes (row, 8 consecutive channels): residual, activation, store.
+  float* epi = (float*)(smem + SMEM_HEAD) + wave * 32 * Cfg::EPI_STRIDE;
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  float sc[TN], sh[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int k = n0 + wn * WTN + j * 32 + col_l;
-    if (k >= p.K) continue;
-    const float sc = p.scale ? p.scale[k] : 1.f;
-    const float sh = p.shift ? p.shift[k] : 0.f;
+    sc[j] = (p.scale && k < p.K) ? p.scale[k] : 1.f;
+    sh[j] = (p.shift && k < p.K) ? p.shift[k] : 0.f;
+  }
+  constexpr int OCT = WTN / 8;                 // channel octets per staged row
+  constexpr int PAIRS = 32 * OCT / 64;         // (row, octet) pairs per lane
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-        if (m >= p.M) continue;
-        float val = fmaf(acc[i][j][v], sc, sh);
-        if (p.res && !p.res_after_act) val += bf16_to_f32(((const bf16_t*)p.res)[(long)m * p.res_stride + k]);
-        val = apply_act(val, p.act);
-        if (p.res && p.res_after_act) val += bf16_to_f32(((const bf16_t*)p.res)[(long)m * p.res_stride + k]);
-        if (p.out_fp32) ((float*)p.y)[(long)m * p.y_stride + k] = val;
-        else ((bf16_t*)p.y)[(long)m * p.y_stride + k] = f32_to_bf16(val);
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] = fmaf(acc[i][j][v], sc[j], sh[j]);
+    // wave-private region: the wave's own LDS writes are visible to its later reads
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < PAIRS; ++t) {
+      const int id = t * 64 + lane;
+      const int row = id / OCT, oct = id - row * OCT;
+      const int m = m0 + wm * WTM + i * 32 + row;
+      const int k = n0 + wn * WTN + oct * 8;
+      if (m < p.M && k < p.K) {
+        const float4 v0 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8);
+        const float4 v1 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8 + 4);
+        float val[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        float rv[8];
+        if (p.res) {
+          const uint4 r4 = *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k);
+          const unsigned ru[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            rv[2 * e] = __uint_as_float(ru[e] << 16);
+            rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
+          }
+          if (!p.res_after_act) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) val[e] += rv[e];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], p.act);
+        if (p.res && p.res_after_act) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] += rv[e];
+        }
+        if (p.out_fp32) {
+          float* yo = (float*)p.y + (long)m * p.y_stride + k;
+          *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
+          *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+        } else {
+          uint4 o;
+          o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
+          o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
+          o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
+          o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
+          *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+        }
       }
     }
   }
 }
 
-struct Variant { int bm, bn; void (*fn)(const ConvGroupArgs); };
+struct Variant { int bm, bn, smem; void (*fn)(const ConvGroupArgs); };
+#define SNA_VARIANT(BM, BN, WM, WN) \
+  { BM, BN, IgemmCfg<BM, BN, WM, WN>::SMEM, igemm_kernel<BM, BN, WM, WN> }
 static const Variant kVariants[] = {
-    {128, 128, igemm_kernel<128, 128, 2, 2>},
-    {128, 64, igemm_kernel<128, 64, 2, 2>},
-    {128, 96, igemm_kernel<128, 96, 4, 1>},
-    {128, 32, igemm_kernel<128, 32, 4, 1>},
-    {64, 64, igemm_kernel<64, 64, 2, 2>},
-    {64, 128, igemm_kernel<64, 128, 1, 4>},
-    {32, 128, igemm_kernel<32, 128, 1, 4>},
+    SNA_VARIANT(128, 128, 2, 2), SNA_VARIANT(128, 64, 2, 2), SNA_VARIANT(128, 96, 4, 1),
+    SNA_VARIANT(128, 32, 4, 1),  SNA_VARIANT(64, 64, 2, 2),  SNA_VARIANT(64, 128, 1, 4),
+    SNA_VARIANT(32, 128, 1, 4),
 };
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-int igemm_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
+int igemm_num_variants() { return kNumVariants; }
 void igemm_tile_shape(int variant, int* bm, int* bn) {
   *bm = kVariants[variant].bm;
   *bn = kVariants[variant].bn;
@@ -201,9 +279,16 @@ void igemm_tile_shape(int variant, int* bm, int* bn) {
 
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s) {
   if (a.n == 0) return hipSuccess;
-  if (variant < 0 || variant >= igemm_num_variants()) return hipErrorInvalidValue;
-  const int blocks = a.p[a.n - 1].tile_start + a.p[a.n - 1].tiles;
-  hipLaunchKernelGGL(kVariants[variant].fn, dim3(blocks), dim3(NTHREADS), 0, s, a);
+  if (variant < 0 || variant >= kNumVariants) return hipErrorInvalidValue;
+  static bool attr_done[kNumVariants] = {false};
+  const Variant& v = kVariants[variant];
+  if (!attr_done[variant]) {
+    hipError_t e = hipFuncSetAttribute((const void*)v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.smem);
+    if (e != hipSuccess) return e;
+    attr_done[variant] = true;
+  }
+  const int blocks = (a.total_tiles + 7) / 8 * 8;
+  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(NTHREADS), v.smem, s, a);
   return hipGetLastError();
 }
 
