@@ -47,6 +47,7 @@ struct ConvProblem {
   int out_fp32;         // 1: y is float (logits), else storage dtype
   int y_stride;         // elements between output rows (>= K); lets a linear write a column block
   int res_stride;
+  unsigned x_bytes, w_bytes;   // extent of x and of the active weight rows, for bounds-checked loads
   int res_after_act;    // 0: y = act(norm(conv) + res); 1: y = act(norm(conv)) + res
 };
 

@@ -133,6 +133,11 @@ struct Fwd {
     p.C8 = p.C / 8; p.K8 = p.R * p.S * p.C8;
     p.magic_c8 = p.C8 > 0 ? (unsigned)(((1u << 24) + p.C8 - 1) / p.C8) : 0;
     p.y_stride = K; p.res_stride = K;
+    const int esize = ti.dtype == SNA_DTYPE_BF16 ? 2 : 4;
+    const double xb = (double)p.N * p.H * p.W * p.C * esize, wb = (double)K * p.wk * esize;
+    if (xb >= 2147483648.0 || wb >= 2147483648.0) err = hipErrorInvalidValue;   // 32-bit buffer offsets
+    p.x_bytes = (unsigned)xb;
+    p.w_bytes = (unsigned)(wb - ((size_t)r0 * p.wr + (size_t)s0 * p.ws) * esize);
   }
 
   static int pick_variant(int M, int K) {

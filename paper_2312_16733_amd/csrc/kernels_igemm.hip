@@ -25,9 +25,10 @@ namespace sna {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int BK = 64;             // reduction elements per LDS stage
-constexpr int LDS_STRIDE = 72;     // bf16 per LDS row: 64 + 8 pad -> 144-byte rows, conflict-free b128 reads
+constexpr int LDS_STRIDE = 64;     // bf16 per LDS row: 128-byte rows, 16-byte chunks XOR-swizzled by (row >> 1) & 7
 constexpr int NTHREADS = 256;
 constexpr int TAP_TABLE = 40;      // entries per tap table (taps <= 32, rest zero)
 constexpr int SMEM_HEAD = 512;     // bytes reserved for the two tap tables
@@ -43,7 +44,7 @@ struct IgemmCfg {
 };
 
 template <int BM, int BN, int WARPS_M, int WARPS_N>
-__global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs args) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void igemm_kernel(const ConvGroupArgs args) {
   using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N>;
   static_assert(WARPS_M * WARPS_N == 4, "4 waves");
   constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs arg
       const int q = m % p.Wo, t = m / p.Wo;
       const int pp = t % p.Ho, n = t / p.Ho;
       const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
-      a_base[i] = ((n * H + ih0) * Wd + iw0) * C;
+      a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;       // bytes
       unsigned mk = 0;
       for (int r = 0; r < p.R; ++r)
         for (int s = 0; s < S; ++s)
@@ -113,43 +114,51 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs arg
   for (int j = 0; j < B_IT; ++j) {
     const int k = n0 + lrow + 32 * j;
     if (k < p.K) b_ok |= 1u << j;
-    b_base[j] = k * p.wk;
+    b_base[j] = k * p.wk * 2;                             // bytes
   }
 
   // reduction position of this thread's unit: tap rs and channel octet c8
   int rs = kc / p.C8;
   int c8 = kc - rs * p.C8;
 
-  uint4 a_reg[A_IT], b_reg[B_IT];
+  uint4 a_reg[2][A_IT], b_reg[2][B_IT];  // two K steps of operands in flight in registers
   const int KT = (p.K8 + 7) >> 3;         // K steps of 64 elements
   __syncthreads();                        // tap tables visible
 
-  auto fetch = [&]() {
+  // Operand loads go through buffer descriptors: an offset at or beyond the tensor's size returns
+  // zeros without touching memory, which is how padding taps, ragged rows and the K tail are fed.
+  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)p.w_bytes, 0x00020000);
+  constexpr unsigned OOB = 0x80000000u;
+  auto fetch = [&](uint4 (&ar)[A_IT], uint4 (&br)[B_IT]) {
     const bool u_ok = rs < RS;
     const int rsc = u_ok ? rs : RS;       // entry RS of the tables is zero
-    const int tx = tap_x[rsc] + c8 * 8, tw = tap_w[rsc] + c8 * 8;
+    const int tx = (tap_x[rsc] + c8 * 8) * 2, tw = (tap_w[rsc] + c8 * 8) * 2;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (u_ok && ((a_mask[i] >> rs) & 1u)) v = *(const uint4*)(X + (a_base[i] + tx));
-      a_reg[i] = v;
+      const bool ok = u_ok && ((a_mask[i] >> rsc) & 1u);
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? (unsigned)(a_base[i] + tx) : OOB, 0, 0);
+      ar[i] = make_uint4(v.x, v.y, v.z, v.w);
     }
 #pragma unroll
     for (int j = 0; j < B_IT; ++j) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (u_ok && ((b_ok >> j) & 1u)) v = *(const uint4*)(Wt + (b_base[j] + tw));
-      b_reg[j] = v;
+      const bool ok = u_ok && ((b_ok >> j) & 1u);
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, ok ? (unsigned)(b_base[j] + tw) : OOB, 0, 0);
+      br[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
     c8 += 8;                              // advance one K step
     while (c8 >= p.C8) { c8 -= p.C8; ++rs; }
   };
-  auto stage = [&](int buf) {
+  // LDS rows are 128 bytes (one K step); the 16-byte chunk c of row r lives in slot c ^ ((r >> 1) & 7),
+  // which keeps both the row-wise stores and the column-wise fragment loads free of bank conflicts.
+  const int kc_sw = kc ^ ((lrow >> 1) & 7);
+  auto stage = [&](int buf, const uint4 (&ar)[A_IT], const uint4 (&br)[B_IT]) {
     bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE;
     bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
-    for (int i = 0; i < A_IT; ++i) *(uint4*)(As + (lrow + 32 * i) * LDS_STRIDE + kc * 8) = a_reg[i];
+    for (int i = 0; i < A_IT; ++i) *(uint4*)(As + (lrow + 32 * i) * LDS_STRIDE + kc_sw * 8) = ar[i];
 #pragma unroll
-    for (int j = 0; j < B_IT; ++j) *(uint4*)(Bs + (lrow + 32 * j) * LDS_STRIDE + kc * 8) = b_reg[j];
+    for (int j = 0; j < B_IT; ++j) *(uint4*)(Bs + (lrow + 32 * j) * LDS_STRIDE + kc_sw * 8) = br[j];
   };
 
   f32x16 acc[TM][TN];
@@ -160,33 +169,54 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const ConvGroupArgs arg
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  fetch();
-  stage(0);
-  __syncthreads();
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) fetch();
-    const bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE;
-    const bf16_t* Bs = As + BM * LDS_STRIDE;
+  const int frag_row = lane & 31, frag_hi = lane >> 5, frag_sw = (frag_row >> 1) & 7;
+  int frag_off[BK / 16];                   // swizzled element offset of this lane's chunk in each 16-wide slice
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 af[TM], bfr[TN];
+  for (int ks = 0; ks < BK / 16; ++ks) frag_off[ks] = ((ks * 2 + frag_hi) ^ frag_sw) * 8;
+  auto compute = [&](int buf) {
+    const bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE + (wm * WTM + frag_row) * LDS_STRIDE;
+    const bf16_t* Bs = tiles + buf * (BM + BN) * LDS_STRIDE + (BM + wn * WTN + frag_row) * LDS_STRIDE;
+    bf16x8 af[2][TM], bfr[2][TN];        // fragments of the next 16-wide slice load while this one multiplies
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *(const bf16x8*)(As + (wm * WTM + i * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
+    for (int i = 0; i < TM; ++i) af[0][i] = *(const bf16x8*)(As + i * 32 * LDS_STRIDE + frag_off[0]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = *(const bf16x8*)(Bs + (wn * WTN + j * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
+    for (int j = 0; j < TN; ++j) bfr[0][j] = *(const bf16x8*)(Bs + j * 32 * LDS_STRIDE + frag_off[0]);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[nxt][i] = *(const bf16x8*)(As + i * 32 * LDS_STRIDE + frag_off[ks + 1]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[nxt][j] = *(const bf16x8*)(Bs + j * 32 * LDS_STRIDE + frag_off[ks + 1]);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < KT) stage(buf ^ 1);
+  };
+
+  // Software pipeline.  At the top of step kt the register sets hold the operands of steps kt+1
+  // and kt+2 (loads in flight); set (kt+1)&1 goes to the idle LDS buffer and is refilled with
+  // step kt+3 before the MFMAs of step kt start, so LDS stores and global loads run under them.
+  fetch(a_reg[0], b_reg[0]);                        // step 0
+  stage(0, a_reg[0], b_reg[0]);
+  if (KT > 1) fetch(a_reg[1], b_reg[1]);            // step 1
+  if (KT > 2) fetch(a_reg[0], b_reg[0]);            // step 2
+  for (int kt = 0; kt < KT; kt += 2) {
     __syncthreads();
+    if (kt + 1 < KT) stage(1, a_reg[1], b_reg[1]);
+    if (kt + 3 < KT) fetch(a_reg[1], b_reg[1]);
+    compute(0);
+    if (kt + 1 >= KT) break;
+    __syncthreads();
+    if (kt + 2 < KT) stage(0, a_reg[0], b_reg[0]);
+    if (kt + 4 < KT) fetch(a_reg[0], b_reg[0]);
+    compute(1);
   }
+  __syncthreads();
 
   // ---- epilogue -----------------------------------------------------------------------------
   // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of a 32x32 tile.
