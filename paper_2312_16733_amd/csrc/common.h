@@ -60,6 +60,7 @@ struct ConvGroupArgs {
 struct PoolProblem {    // max pool 3x3/2 or global average pool
   const void* x; void* y;
   int N, H, W, C, Ho, Wo;
+  int out_fp32;         // global average pool only: write fp32 instead of the storage dtype
   int tile_start, tiles;
 };
 struct PoolGroupArgs { int n; PoolProblem p[SNA_MAX_GROUPS]; };

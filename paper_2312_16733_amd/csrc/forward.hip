@@ -260,6 +260,46 @@ struct Fwd {
     else launch(KC_POOL, 0, bytes, [&] { return launch_gap(a, dt, stream); });
   }
 
+  void dw_slot(const std::function<bool(Group&, DwProblem&)>& fill) {
+    DwGroupArgs a;
+    a.n = 0;
+    double flops = 0, bytes = 0;
+    for (Group& g : groups) {
+      DwProblem p;
+      memset(&p, 0, sizeof(p));
+      if (!fill(g, p)) continue;
+      flops += 2.0 * p.N * p.Ho * p.Wo * p.C * p.k * p.k;
+      macs += (int64_t)p.N * p.Ho * p.Wo * p.C * p.k * p.k;
+      bytes += 2.0 * p.N * p.C * ((double)p.H * p.W + (double)p.Ho * p.Wo) + 2.0 * p.k * p.k * p.C + 8.0 * p.C;
+      a.p[a.n++] = p;
+    }
+    if (a.n) launch(KC_DEPTHWISE, flops, bytes, [&] { return launch_depthwise(a, stream); });
+  }
+  // Depthwise WeightSlice: leading C channels, centre k x k window of the stored kernel.
+  void slice_dw(DwProblem& p, const sna_tensor_info& ti, int k, int stride) {
+    const int rmax = ti.dims[0], smax = ti.dims[1], cmax = ti.dims[2];
+    p.wr = smax * cmax; p.ws = cmax;
+    const int r0 = (rmax - k) / 2, s0 = (smax - k) / 2;
+    p.w = wptr(ti) + ((size_t)r0 * p.wr + (size_t)s0 * p.ws) * 2;
+    p.k = k; p.stride = stride; p.pad = k / 2;
+    p.Ho = out_size(p.H, k, stride); p.Wo = out_size(p.W, k, stride);
+  }
+  void se_slot(const std::function<bool(Group&, SeProblem&)>& fill) {
+    SeGroupArgs a;
+    a.n = 0;
+    double flops = 0, bytes = 0;
+    for (Group& g : groups) {
+      SeProblem p;
+      memset(&p, 0, sizeof(p));
+      if (!fill(g, p)) continue;
+      flops += 4.0 * p.N * p.C * p.Q;
+      macs += (int64_t)2 * p.N * p.C * p.Q;
+      bytes += 4.0 * p.N * p.HW * p.C + 4.0 * p.C * p.Q;
+      a.p[a.n++] = p;
+    }
+    if (a.n) launch(KC_SE, flops, bytes, [&] { return launch_se(a, stream); });
+  }
+
   // ---- request gather / logits scatter -----------------------------------------------------
   void copy_items(const void* src, void* dst, std::vector<CopyItem>& items) {
     for (size_t i = 0; i < items.size(); i += SNA_COPY_ITEMS) {
@@ -442,7 +482,127 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
   return SNA_OK;
 }
 
-sna_status Fwd::run_mbv3(const void*, float*) { return fail(SNA_E_ARCH, "MBV3 forward is not built"); }
+// ------------------------------------------------------------------------------------------
+// MBV3-shaped SuperNet: stem, fixed depthwise-separable block, inverted-residual stages, head
+// ------------------------------------------------------------------------------------------
+sna_status Fwd::run_mbv3(const void*, float* logits) {
+  const sna_arch_desc& a = T().arch;
+  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = a.in_ch; }
+  auto sn = [&](ConvProblem& p, const std::string& name, const Group& g) {
+    p.scale = scale_of(name, g.cfg->subnet_id); p.shift = shift_of(name, g.cfg->subnet_id);
+  };
+  conv_slot(true, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    slice_conv(p, tensor("stem.w"), a.stem_ch, 3, 2);
+    sn(p, "stem.sn", g);
+    p.act = SNA_ACT_HSWISH; p.y = g.buf[0];
+    g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
+    return true;
+  });
+  // fixed first block: depthwise 3x3 + SN + ReLU -> 1x1 + SN, residual
+  dw_slot([&](Group& g, DwProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    slice_dw(p, tensor("first.dw.w"), 3, 1);
+    p.scale = scale_of("first.sn1", g.cfg->subnet_id); p.shift = shift_of("first.sn1", g.cfg->subnet_id);
+    p.act = SNA_ACT_RELU; p.y = g.buf[2];
+    return true;
+  });
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
+    p.x = g.buf[2]; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    slice_conv(p, tensor("first.pw.w"), a.stem_ch, 1, 1);
+    sn(p, "first.sn2", g);
+    p.act = SNA_ACT_NONE; p.res = g.cur; p.y = g.buf[1];
+    g.cur = p.y; g.cur_buf = 1;
+    return true;
+  });
+  for (int s = 0; s < a.n_stages; ++s)
+    for (int j = 0; j < a.stage_max_depth[s]; ++j) {
+      const std::string pre = "s" + std::to_string(s) + ".b" + std::to_string(j) + ".";
+      const int st = j == 0 ? a.stage_stride[s] : 1;
+      const int act = a.stage_act[s];
+      auto on = [&](const Group& g) { return j < g.cfg->depth[s]; };      // LayerSelect
+      conv_slot(false, [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+        slice_conv(p, tensor(pre + "expand.w"), g.cfg->block_mid_ch[s][j], 1, 1);
+        sn(p, pre + "sn1", g);
+        p.act = act; p.y = g.buf[2];
+        return true;
+      });
+      dw_slot([&](Group& g, DwProblem& p) {
+        if (!on(g)) return false;
+        p.x = g.buf[2]; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.cfg->block_mid_ch[s][j];
+        slice_dw(p, tensor(pre + "dw.w"), g.cfg->block_kernel[s][j], st);
+        p.scale = scale_of(pre + "sn2", g.cfg->subnet_id); p.shift = shift_of(pre + "sn2", g.cfg->subnet_id);
+        p.act = act; p.y = g.buf[3];
+        return true;
+      });
+      if (a.stage_se[s]) {
+        pool_slot(false, [&](Group& g, PoolProblem& p) {
+          if (!on(g)) return false;
+          p.x = g.buf[3]; p.N = g.n; p.H = out_size(g.H, 3, st); p.W = out_size(g.W, 3, st);
+          p.C = g.cfg->block_mid_ch[s][j]; p.y = g.small; p.out_fp32 = 1;
+          return true;
+        });
+        se_slot([&](Group& g, SeProblem& p) {
+          if (!on(g)) return false;
+          const int m = g.cfg->block_mid_ch[s][j];
+          const sna_tensor_info& t1 = tensor(pre + "se.fc1.w");
+          const sna_tensor_info& t2 = tensor(pre + "se.fc2.w");
+          p.x = g.buf[3]; p.y = g.buf[3];
+          p.w1 = wptr(t1); p.b1 = (const float*)wptr(tensor(pre + "se.fc1.b")); p.w1_stride = t1.dims[1];
+          p.w2 = wptr(t2); p.b2 = (const float*)wptr(tensor(pre + "se.fc2.b")); p.w2_stride = t2.dims[1];
+          p.pooled = g.small; p.gate = g.small + (size_t)g.n * m;
+          p.N = g.n; p.HW = out_size(g.H, 3, st) * out_size(g.W, 3, st); p.C = m; p.Q = g.cfg->block_aux_ch[s][j];
+          return true;
+        });
+      }
+      conv_slot(false, [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        const int co = a.stage_ch[s];
+        p.x = g.buf[3]; p.N = g.n; p.H = out_size(g.H, 3, st); p.W = out_size(g.W, 3, st);
+        p.C = g.cfg->block_mid_ch[s][j];
+        slice_conv(p, tensor(pre + "project.w"), co, 1, 1);
+        sn(p, pre + "sn3", g);
+        p.act = SNA_ACT_NONE;
+        if (st == 1 && g.C == co) p.res = g.cur;
+        const int dst = g.cur_buf == 0 ? 1 : 0;
+        p.y = g.buf[dst];
+        g.cur = p.y; g.cur_buf = dst; g.H = p.H; g.W = p.W; g.C = co;
+        return true;
+      });
+    }
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+    slice_conv(p, tensor("tail.w"), a.tail_ch, 1, 1);
+    sn(p, "tail.sn", g);
+    p.act = SNA_ACT_HSWISH; p.y = g.buf[2];
+    g.cur = p.y; g.C = a.tail_ch;
+    return true;
+  });
+  pool_slot(false, [&](Group& g, PoolProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C; p.y = g.buf[3];
+    g.cur = p.y; g.H = g.W = 1;
+    return true;
+  });
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = 1; p.W = 1; p.C = g.C;
+    slice_conv(p, tensor("fc1.w"), a.fc_ch, 1, 1);
+    p.shift = (const float*)wptr(tensor("fc1.b"));
+    p.act = SNA_ACT_HSWISH; p.y = g.buf[4];
+    g.cur = p.y; g.C = a.fc_ch;
+    return true;
+  });
+  conv_slot(a.n_classes % 8 != 0, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = 1; p.W = 1; p.C = g.C;
+    slice_conv(p, tensor("head.w"), a.n_classes, 1, 1);
+    p.shift = (const float*)wptr(tensor("head.b"));
+    p.y = logits_target(g, logits); p.out_fp32 = 1;
+    return true;
+  });
+  scatter_logits(logits);
+  return SNA_OK;
+}
 sna_status Fwd::run_transformer(const void*, float*, void*) {
   return fail(SNA_E_ARCH, "TRANSFORMER forward is not built");
 }

@@ -205,13 +205,14 @@ __global__ __launch_bounds__(256) void gap_kernel(const PoolGroupArgs args) {
   __syncthreads();
   if (hl == 0 && cv < cvn) {
     const float inv = 1.f / (float)HW;
-    T* y = (T*)p.y + (long)n * p.C + cv * VEC;
+    const long yo = (long)n * p.C + cv * VEC;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += red[j][threadIdx.x & 31][i];
-      st_f32<T>(y + i, sum * inv);
+      if (p.out_fp32) ((float*)p.y)[yo + i] = sum * inv;
+      else st_f32<T>((T*)p.y + yo + i, sum * inv);
     }
   }
 }

@@ -1,0 +1,200 @@
+// Depthwise WeightSlice convolution (centre k x k window of a stored 7x7, leading channels) with
+// fused SubnetNorm + activation, and the squeeze-excite gate.  All of it is HBM-bound streaming:
+// threads own 8 consecutive channels (16-byte loads / stores, channel-fastest across lanes).
+#include "common.h"
+
+namespace sna {
+
+__device__ __forceinline__ void unpack8(const uint4 v, float* f) {
+  const unsigned u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f[2 * e] = __uint_as_float(u[e] << 16);
+    f[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 o;
+  o.x = (unsigned)f32_to_bf16(f[0]) | ((unsigned)f32_to_bf16(f[1]) << 16);
+  o.y = (unsigned)f32_to_bf16(f[2]) | ((unsigned)f32_to_bf16(f[3]) << 16);
+  o.z = (unsigned)f32_to_bf16(f[4]) | ((unsigned)f32_to_bf16(f[5]) << 16);
+  o.w = (unsigned)f32_to_bf16(f[6]) | ((unsigned)f32_to_bf16(f[7]) << 16);
+  return o;
+}
+
+// ---------------------------------------------------------------------------------------------
+// One thread = TW adjacent output pixels of one row x 8 channels.  For every kernel row the
+// thread loads the (TW-1)*STRIDE + K input columns it needs once and reuses them across its TW
+// outputs, so an input element is fetched K (not K*K) times per output row from L1/L2 and once
+// from HBM.  y = act(scale[c] * sum_{r,s} x * w[r0+r][s0+s][c] + shift[c]).
+// ---------------------------------------------------------------------------------------------
+constexpr int DW_TW = 4;
+
+template <int K, int STRIDE>
+__global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) {
+  const int g = find_problem(args, blockIdx.x);
+  const DwProblem& p = args.p[g];
+  const int c8n = p.C >> 3;
+  const int strips = (p.Wo + DW_TW - 1) / DW_TW;
+  const long idx = (long)(blockIdx.x - p.tile_start) * 256 + threadIdx.x;
+  const long total = (long)p.N * p.Ho * strips * c8n;
+  if (idx >= total) return;
+  const int c8 = idx % c8n;
+  long t = idx / c8n;
+  const int qs = t % strips; t /= strips;
+  const int pp = t % p.Ho;
+  const int n = t / p.Ho;
+  const int q0 = qs * DW_TW;
+  constexpr int COLS = (DW_TW - 1) * STRIDE + K;
+  constexpr int PAD = K / 2;
+  const bf16_t* x = (const bf16_t*)p.x + (long)n * p.H * p.W * p.C + c8 * 8;
+  const bf16_t* w = (const bf16_t*)p.w + c8 * 8;           // already at the centre window's first tap
+  float acc[DW_TW][8];
+#pragma unroll
+  for (int o = 0; o < DW_TW; ++o)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[o][e] = 0.f;
+  const int iw0 = q0 * STRIDE - PAD;
+#pragma unroll
+  for (int r = 0; r < K; ++r) {
+    const int ih = pp * STRIDE + r - PAD;
+    if (ih < 0 || ih >= p.H) continue;
+    uint4 col[COLS];
+#pragma unroll
+    for (int cidx = 0; cidx < COLS; ++cidx) {
+      const int iw = iw0 + cidx;
+      col[cidx] = (iw >= 0 && iw < p.W) ? *(const uint4*)(x + ((long)ih * p.W + iw) * p.C) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int s = 0; s < K; ++s) {
+      float wv[8];
+      unpack8(*(const uint4*)(w + (long)r * p.wr + (long)s * p.ws), wv);
+#pragma unroll
+      for (int o = 0; o < DW_TW; ++o) {
+        float xv[8];
+        unpack8(col[o * STRIDE + s], xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(xv[e], wv[e], acc[o][e]);
+      }
+    }
+  }
+  float sc[8], sh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sc[e] = p.scale[c8 * 8 + e]; sh[e] = p.shift[c8 * 8 + e]; }
+  bf16_t* y = (bf16_t*)p.y + (((long)n * p.Ho + pp) * p.Wo) * p.C + c8 * 8;
+#pragma unroll
+  for (int o = 0; o < DW_TW; ++o) {
+    if (q0 + o >= p.Wo) break;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = apply_act(fmaf(acc[o][e], sc[e], sh[e]), p.act);
+    *(uint4*)(y + (long)(q0 + o) * p.C) = pack8(v);
+  }
+}
+
+hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s) {
+  // one launch per (kernel size, stride) present among the problems
+  for (int k = 3; k <= 7; k += 2)
+    for (int st = 1; st <= 2; ++st) {
+      DwGroupArgs b;
+      b.n = 0;
+      int start = 0;
+      for (int i = 0; i < a.n; ++i) {
+        if (a.p[i].k != k || a.p[i].stride != st) continue;
+        DwProblem p = a.p[i];
+        const long strips = (p.Wo + DW_TW - 1) / DW_TW;
+        p.tiles = (int)(((long)p.N * p.Ho * strips * (p.C / 8) + 255) / 256);
+        p.tile_start = start;
+        start += p.tiles;
+        b.p[b.n++] = p;
+      }
+      if (!b.n) continue;
+#define SNA_DW(KK, SS) if (k == KK && st == SS) hipLaunchKernelGGL((depthwise_kernel<KK, SS>), dim3(start), dim3(256), 0, s, b)
+      SNA_DW(3, 1); SNA_DW(3, 2); SNA_DW(5, 1); SNA_DW(5, 2); SNA_DW(7, 1); SNA_DW(7, 2);
+#undef SNA_DW
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Squeeze-excite gate, one block per request:
+//   z = pooled[n][:C] (fp32 mean over pixels, computed by the pooling kernel)
+//   h = relu(W1[:Q,:C] z + b1[:Q]);  gate = hardsigmoid(W2[:C,:Q] h + b2[:C])
+// A wave owns an output and strides over the reduction with 64 lanes, then reduces in a fixed
+// butterfly order.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void se_gate_kernel(const SeGroupArgs args) {
+  __shared__ float zs[1024];
+  __shared__ float hs[256];
+  const int g = find_problem(args, blockIdx.x);
+  const SeProblem& p = args.p[g];
+  const int n = blockIdx.x - p.tile_start;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int c = threadIdx.x; c < p.C; c += 256) zs[c] = p.pooled[(long)n * p.C + c];
+  __syncthreads();
+  const bf16_t* w1 = (const bf16_t*)p.w1;
+  for (int q = wave; q < p.Q; q += 4) {
+    float a = 0.f;
+    for (int c = lane; c < p.C; c += 64) a = fmaf(bf16_to_f32(w1[(long)q * p.w1_stride + c]), zs[c], a);
+    a = wave_sum(a);
+    if (lane == 0) hs[q] = fmaxf(a + p.b1[q], 0.f);
+  }
+  __syncthreads();
+  const bf16_t* w2 = (const bf16_t*)p.w2;
+  for (int c = wave; c < p.C; c += 4) {
+    float a = 0.f;
+    for (int q = lane; q < p.Q; q += 64) a = fmaf(bf16_to_f32(w2[(long)c * p.w2_stride + q]), hs[q], a);
+    a = wave_sum(a);
+    if (lane == 0) p.gate[(long)n * p.C + c] = fminf(fmaxf(a + p.b2[c] + 3.f, 0.f), 6.f) * (1.f / 6.f);
+  }
+}
+
+// y[n, hw, c] = bf16(x[n, hw, c] * gate[n, c])
+__global__ __launch_bounds__(256) void se_scale_kernel(const SeGroupArgs args) {
+  const int g = find_problem(args, blockIdx.x);
+  const SeProblem& p = args.p[g];
+  const int c8n = p.C >> 3;
+  const long idx = (long)(blockIdx.x - p.tile_start) * 256 + threadIdx.x;
+  const long total = (long)p.N * p.HW * c8n;
+  if (idx >= total) return;
+  const int c8 = idx % c8n;
+  const long pix = idx / c8n;
+  const int n = pix / p.HW;
+  float v[8];
+  unpack8(*(const uint4*)((const bf16_t*)p.x + pix * p.C + c8 * 8), v);
+  const float* gt = p.gate + (long)n * p.C + c8 * 8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] *= gt[e];
+  *(uint4*)((bf16_t*)p.y + pix * p.C + c8 * 8) = pack8(v);
+}
+
+hipError_t launch_se(const SeGroupArgs& a, hipStream_t s) {
+  if (a.n == 0) return hipSuccess;
+  SeGroupArgs b = a;
+  int start = 0;
+  for (int i = 0; i < b.n; ++i) {
+    if (b.p[i].C > 1024 || b.p[i].Q > 256) return hipErrorInvalidValue;
+    b.p[i].tile_start = start; b.p[i].tiles = b.p[i].N; start += b.p[i].N;
+  }
+  hipLaunchKernelGGL(se_gate_kernel, dim3(start), dim3(256), 0, s, b);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  start = 0;
+  for (int i = 0; i < b.n; ++i) {
+    const long total = (long)b.p[i].N * b.p[i].HW * (b.p[i].C / 8);
+    b.p[i].tiles = (int)((total + 255) / 256);
+    b.p[i].tile_start = start; start += b.p[i].tiles;
+  }
+  hipLaunchKernelGGL(se_scale_kernel, dim3(start), dim3(256), 0, s, b);
+  return hipGetLastError();
+}
+
+}  // namespace sna

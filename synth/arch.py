@@ -168,6 +168,7 @@ class MBV3Spec:
     res_choices: Tuple[int, ...] = (160, 192, 224)
     tail_ch: int = 960
     fc_ch: int = 1280
+    init_gain: float = 1.0      # weights N(0, init_gain / fan_in), see weights.py
 
     @property
     def n_stages(self):

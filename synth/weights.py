@@ -1,7 +1,12 @@
 """Random-init SuperNet weights, SubnetNorm statistics and request inputs.
 
 Distributions (second parameter of N(.,.) is a variance):
-  conv / depthwise / linear weights  N(0, 2 / fan_in), fan_in at max size
+  conv / depthwise / linear weights  N(0, gain / fan_in), fan_in at max size; gain = 2 except
+                                     for the MBV3 family, whose spec sets gain = 1: with gain 2
+                                     its un-rectified project -> expand pairs compound to 1e4-scale
+                                     activations that saturate the squeeze-excite hard-sigmoid
+                                     gates, and the forward becomes ill-conditioned (a one-ulp input
+                                     change moves the logits by > 10 %)
   biases                             N(0, 0.01)
   SubnetNorm per (subnet, layer):    mean N(0, 0.1), var U(0.5, 1.5),
                                      gamma U(0.5, 1.5), beta N(0, 0.1)
@@ -28,10 +33,11 @@ def to_bf16_values(a: np.ndarray) -> np.ndarray:
 
 def make_weights(spec, seed: int) -> dict:
     out = {}
+    gain = float(getattr(spec, "init_gain", 2.0))
     for td in spec.tensors():
         g = keyed_rng(seed, "w:" + td.name)
         if td.kind in ("conv", "dw", "linear"):
-            a = g.standard_normal(td.shape, dtype=np.float32) * np.float32(np.sqrt(2.0 / td.fan_in))
+            a = g.standard_normal(td.shape, dtype=np.float32) * np.float32(np.sqrt(gain / td.fan_in))
             if spec.dtype == "bf16":
                 a = to_bf16_values(a)
         elif td.kind == "bias":

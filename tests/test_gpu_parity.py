@@ -203,3 +203,69 @@ def test_error_paths(torch_mod, resnet_full):
     got = net.forward([C[0]], [0], x)                     # handle still usable
     torch.cuda.synchronize()
     assert np.all(np.isfinite(got.cpu().numpy()))
+
+
+# ------------------------------------------------------------------ cfg 3: MBV3-shaped, bf16
+@pytest.fixture(scope="module")
+def mbv3_full(torch_mod):
+    import paper_2312_16733_amd as sna
+    spec = synth.MBV3Spec()
+    W, S, C = setup(spec, 16)
+    net = sna.Supernet(spec, W, S, 16, 64)
+    yield spec, W, S, C, net
+    net.close()
+
+
+def test_mbv3_small_resolutions_all_cfgs(torch_mod):
+    """Odd, small resolutions: ragged strips in the depthwise kernel, every kernel size and stride."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.MBV3Spec(res_choices=(40, 48, 57))
+    W, S, C = setup(spec, 10)
+    net = sna.Supernet(spec, W, S, 10, 8)
+    for c in C:
+        x = synth.make_inputs(spec, 3, c.in_h, c.in_w, 7)
+        say("mbv3-small cfg", c.subnet_id, c.depth, c.in_h, [k[:d] for k, d in zip(c.block_kernel, c.depth)])
+        got = run_single(torch, net, spec, c, x)
+        e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"mbv3 small cfg {c.subnet_id}")
+        say("   rel err %.3e undecided %d" % (e, und))
+    net.close()
+
+
+@pytest.mark.parametrize("ci,batch", [(0, 1), (0, 16), (4, 2), (8, 3), (11, 1), (15, 1), (15, 4)])
+def test_mbv3_full_supernet(torch_mod, mbv3_full, ci, batch):
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = mbv3_full
+    c = C[ci]
+    x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 21)
+    say("mbv3 cfg", ci, "batch", batch, "res", c.in_h, c.depth)
+    got = run_single(torch, net, spec, c, x)
+    e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"mbv3 cfg {ci} b{batch}")
+    say("   rel err %.3e undecided %d" % (e, und))
+
+
+def test_mbv3_batch64_sampled_and_mixed(torch_mod, mbv3_full):
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = mbv3_full
+    c = C[9]
+    x = synth.make_inputs(spec, 64, c.in_h, c.in_w, 22)
+    got = run_single(torch, net, spec, c, x)
+    for r in (0, 31, 63):
+        check_parity(got[r:r + 1], oracle.forward(spec, W, S, c, x[r:r + 1]), "bf16", f"mbv3 b64 req {r}")
+    np.testing.assert_array_equal(run_single(torch, net, spec, c, x[7:8])[0], got[7])
+    # mixed-subnet batch with mixed resolutions
+    route = synth.zipf_assignment(24, 16, 9)
+    xs = [synth.make_inputs(spec, 1, C[ci].in_h, C[ci].in_w, 300 + r) for r, ci in enumerate(route)]
+    flat = np.concatenate([a.ravel() for a in xs])
+    mixed = net.forward(C, route, to_dev(torch, spec, flat))
+    torch.cuda.synchronize()
+    mixed = mixed.cpu().numpy()
+    for ci in sorted(set(route.tolist())):
+        idx = np.nonzero(route == ci)[0]
+        single = run_single(torch, net, spec, C[ci], np.concatenate([xs[r] for r in idx]))
+        np.testing.assert_array_equal(mixed[idx], single, err_msg=f"cfg {ci}")
+    for r in (0, 11, 23):
+        check_parity(mixed[r:r + 1], oracle.forward(spec, W, S, C[route[r]], xs[r]), "bf16", f"mbv3 mixed req {r}")
