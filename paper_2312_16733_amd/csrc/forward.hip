@@ -181,6 +181,11 @@ struct Fwd {
       double flops = 0, bytes = 0;
       for (size_t i = 0; i < ps.size(); ++i) {
         if (var[i] != v) continue;
+        if (a.n == SNA_MAX_GROUPS) {       // more problems than one launch carries: flush
+          a.total_tiles = start;
+          launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, stream); });
+          a.n = 0; start = 0; flops = 0; bytes = 0;
+        }
         ConvProblem& p = ps[i];
         p.tiles_n = (p.K + bn - 1) / bn;
         p.tiles = ((p.M + bm - 1) / bm) * p.tiles_n;
@@ -603,8 +608,116 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
   scatter_logits(logits);
   return SNA_OK;
 }
-sna_status Fwd::run_transformer(const void*, float*, void*) {
-  return fail(SNA_E_ARCH, "TRANSFORMER forward is not built");
+// ------------------------------------------------------------------------------------------
+// TRANSFORMER: post-LayerNorm encoder layers; leading heads / leading FFN columns per layer
+// ------------------------------------------------------------------------------------------
+sna_status Fwd::run_transformer(const void*, float* logits, void* hidden) {
+  const sna_arch_desc& a = T().arch;
+  const int hd = a.hidden, S = a.seq_len;
+  // buffers: x in buf[0] / buf[1] (or the caller's input), q k v ctx u ffn in buf[2..7]
+  auto linear = [&](Group& g, ConvProblem& p, const void* x, int c_in, const std::string& w, int n_out,
+                    const std::string& bias, int act, const void* res, void* y) {
+    memset(&p, 0, sizeof(p));
+    p.x = x; p.N = g.n * S; p.H = 1; p.W = 1; p.C = c_in;
+    slice_conv(p, tensor(w), n_out, 1, 1);
+    p.shift = (const float*)wptr(tensor(bias));
+    p.act = act; p.res = res; p.y = y;
+  };
+  auto layernorm = [&](const std::string& gname, const std::string& bname, int j, int src, bool to_cur_other) {
+    LnGroupArgs la;
+    la.n = 0;
+    double bytes = 0;
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;
+      LnProblem p;
+      memset(&p, 0, sizeof(p));
+      p.x = g.buf[src];
+      p.gamma = (const float*)wptr(tensor(gname)); p.beta = (const float*)wptr(tensor(bname));
+      const int dst = g.cur_buf == 0 ? 1 : 0;
+      p.y = g.buf[dst];
+      p.rows = g.n * S; p.cols = hd;
+      g.cur = p.y; g.cur_buf = dst;
+      bytes += 4.0 * p.rows * p.cols + 8.0 * p.cols;
+      la.p[la.n++] = p;
+    }
+    (void)to_cur_other;
+    if (la.n) launch(KC_LAYERNORM, 0, bytes, [&] { return launch_layernorm(la, stream); });
+  };
+  for (int j = 0; j < a.max_layers; ++j) {
+    const std::string pre = "l" + std::to_string(j) + ".";
+    std::vector<ConvProblem> ps;
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;                 // LayerSelect
+      const int at = g.cfg->block_mid_ch[0][j];
+      ConvProblem p;
+      linear(g, p, g.cur, hd, pre + "q.w", at, pre + "q.b", SNA_ACT_NONE, nullptr, g.buf[2]); ps.push_back(p);
+      linear(g, p, g.cur, hd, pre + "k.w", at, pre + "k.b", SNA_ACT_NONE, nullptr, g.buf[3]); ps.push_back(p);
+      linear(g, p, g.cur, hd, pre + "v.w", at, pre + "v.b", SNA_ACT_NONE, nullptr, g.buf[4]); ps.push_back(p);
+    }
+    if (ps.empty()) continue;
+    run_igemm(ps);
+    AttnGroupArgs aa;
+    aa.n = 0;
+    double aflops = 0, abytes = 0;
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;
+      const int at = g.cfg->block_mid_ch[0][j];
+      AttnProblem p;
+      memset(&p, 0, sizeof(p));
+      p.q = g.buf[2]; p.k = g.buf[3]; p.v = g.buf[4]; p.o = g.buf[5];
+      p.B = g.n; p.S = S; p.heads = at / a.head_dim; p.ld = at;
+      aflops += 4.0 * p.B * p.heads * S * S * a.head_dim;
+      macs += (int64_t)2 * p.B * p.heads * S * S * a.head_dim;
+      abytes += 2.0 * 4 * p.B * S * at;
+      aa.p[aa.n++] = p;
+    }
+    launch(KC_ATTENTION, aflops, abytes, [&] { return launch_attention(aa, stream); });
+    ps.clear();
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;
+      ConvProblem p;
+      linear(g, p, g.buf[5], g.cfg->block_mid_ch[0][j], pre + "o.w", hd, pre + "o.b", SNA_ACT_NONE, g.cur, g.buf[6]);
+      ps.push_back(p);
+    }
+    run_igemm(ps);
+    layernorm(pre + "ln1.g", pre + "ln1.b", j, 6, true);
+    ps.clear();
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;
+      ConvProblem p;
+      linear(g, p, g.cur, hd, pre + "ffn1.w", g.cfg->block_aux_ch[0][j], pre + "ffn1.b", SNA_ACT_GELU, nullptr, g.buf[7]);
+      ps.push_back(p);
+    }
+    run_igemm(ps);
+    ps.clear();
+    for (Group& g : groups) {
+      if (j >= g.cfg->depth[0]) continue;
+      ConvProblem p;
+      linear(g, p, g.buf[7], g.cfg->block_aux_ch[0][j], pre + "ffn2.w", hd, pre + "ffn2.b", SNA_ACT_NONE, g.cur, g.buf[6]);
+      ps.push_back(p);
+    }
+    run_igemm(ps);
+    layernorm(pre + "ln2.g", pre + "ln2.b", j, 6, true);
+  }
+  // logits from token 0 of every request: a 1x1 "conv" over [n][S][1][hidden] with stride S
+  conv_slot(a.n_classes % 8 != 0, [&](Group& g, ConvProblem& p) {
+    p.x = g.cur; p.N = g.n; p.H = S; p.W = 1; p.C = hd;
+    slice_conv(p, tensor("head.w"), a.n_classes, 1, S);
+    p.Wo = 1; p.M = p.N * p.Ho * p.Wo;
+    p.shift = (const float*)wptr(tensor("head.b"));
+    p.y = logits_target(g, logits); p.out_fp32 = 1;
+    return true;
+  });
+  scatter_logits(logits);
+  if (hidden) {
+    const size_t rb = (size_t)S * hd * T().esz;
+    for (Group& g : groups) {
+      std::vector<CopyItem> items;
+      for (int i = 0; i < g.n; ++i) items.push_back({(size_t)i * rb, (size_t)g.reqs[i] * rb, rb});
+      copy_items(g.cur, hidden, items);
+    }
+  }
+  return SNA_OK;
 }
 
 static size_t folded_bytes(const ArchTables& T, int n_subnets) {
