@@ -41,6 +41,7 @@ struct ConvProblem {
   int M;                // N*Ho*Wo
   int C8, K8;           // C/8, R*S*C/8 (igemm only)
   unsigned magic_c8;    // ceil(2^24 / C8)
+  int inv_s;            // ceil(2^16 / S): tap row r = (rs * inv_s) >> 16
   int tiles_n;          // tiles along K (igemm)
   int tile_start, tiles;
   int act;              // sna_act

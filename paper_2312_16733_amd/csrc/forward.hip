@@ -132,6 +132,7 @@ struct Fwd {
     p.M = p.N * p.Ho * p.Wo;
     p.C8 = p.C / 8; p.K8 = p.R * p.S * p.C8;
     p.magic_c8 = p.C8 > 0 ? (unsigned)(((1u << 24) + p.C8 - 1) / p.C8) : 0;
+    p.inv_s = (65536 + p.S - 1) / p.S;
     p.y_stride = K; p.res_stride = K;
     const int esize = ti.dtype == SNA_DTYPE_BF16 ? 2 : 4;
     const double xb = (double)p.N * p.H * p.W * p.C * esize, wb = (double)K * p.wk * esize;
@@ -140,26 +141,23 @@ struct Fwd {
     p.w_bytes = (unsigned)(wb - ((size_t)r0 * p.wr + (size_t)s0 * p.ws) * esize);
   }
 
-  static int pick_variant(int M, int K) {
+  // Tile choice (measured on MI355X): 128-row tiles with two blocks per CU; the column tile that
+  // pads the active out-channels least, wider for deep reductions; 64-row tiles when a layer has
+  // too few 128-row tiles to fill 256 CUs; 32 rows for head-sized M.
+  static int pick_variant(int M, int K, int depth) {
     // variants: 0 128x128, 1 128x64, 2 128x96, 3 128x32, 4 64x64, 5 64x128, 6 32x128
     if (M <= 32) return 6;
-    int bn;
-    if (K <= 32) bn = 32;
-    else if (K <= 64) bn = 64;
-    else if (K <= 96) bn = 96;
-    else if (K <= 128) bn = 128;
-    else {
-      const int cand[3] = {128, 96, 64};
-      int best = 128, waste = 1 << 30;
-      for (int c : cand) {
-        const int w = (K + c - 1) / c * c - K;
-        if (w < waste) { waste = w; best = c; }
-      }
-      bn = best;
+    if (K <= 32) return 3;
+    int bn = 128, best = 1 << 30;
+    const int cand[3] = {128, 96, 64};
+    for (int c : cand) {
+      const int padded = (K + c - 1) / c * c;
+      const bool better = padded < best || (padded == best && depth < 1024);   // ties: narrower for shallow K
+      if (better) { best = padded; bn = c; }
     }
     const long tiles128 = (long)((M + 127) / 128) * ((K + bn - 1) / bn);
-    if (tiles128 < 256 && (bn == 64 || bn == 128)) return bn == 64 ? 4 : 5;
-    return bn == 128 ? 0 : (bn == 64 ? 1 : (bn == 96 ? 2 : 3));
+    if (tiles128 < 256) return K <= 64 ? 4 : 5;
+    return bn == 128 ? 0 : (bn == 64 ? 1 : 2);
   }
 
   void run_igemm(std::vector<ConvProblem>& ps) {
@@ -171,7 +169,7 @@ struct Fwd {
         err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
         return;
       }
-      var[i] = pick_variant(q.M, q.K);
+      var[i] = pick_variant(q.M, q.K, q.C * q.R * q.S);
     }
     for (int v = 0; v < igemm_num_variants(); ++v) {
       ConvGroupArgs a;

@@ -10,14 +10,17 @@
 // not for the SuperNet's.  Active channel counts are multiples of 8, so a unit never straddles a
 // tap and every 16-byte load is aligned.
 //
-// Tiling: 256 threads = 4 waves; block tile BM x BN, K step 64, double-buffered LDS (one barrier
-// per step) with the next step's global loads in flight during the MFMAs;
-// v_mfma_f32_32x32x16_bf16, fp32 accumulators.  Per-thread addressing is set up once: a base
-// offset and a tap-validity bitmask per fetched row, tap offsets in a small LDS table; the K loop
-// only adds.  The epilogue (fused SubnetNorm scale/shift, residual, activation) goes through a
-// per-wave fp32 LDS tile so that residual loads and output stores are 16 bytes per lane and
-// contiguous along channels.  Blocks are renumbered so that consecutive tiles (which share
-// activation rows) run on the same XCD and meet in its L2.
+// Data path: operands go from global memory straight into LDS (buffer loads with the LDS
+// destination, 16 bytes per lane; an out-of-range offset writes zeros, which feeds padding taps,
+// ragged rows and the K tail).  LDS holds a ring of NS stages of one K step (64 elements) each;
+// rows are 128 bytes with the 16-byte chunks XOR-swizzled by (row >> 1) & 7 so that both the
+// linear DMA writes and the column-wise fragment reads are bank-conflict free.  Loads for step
+// kt + NS - 1 are issued before the MFMAs of step kt; waits are explicit (s_waitcnt vmcnt with
+// the number of newer loads still allowed in flight, then s_barrier).  Fragment reads are
+// software-pipelined one 16-wide slice ahead of the v_mfma_f32_32x32x16_bf16 that use them.
+// The epilogue (fused SubnetNorm scale/shift, residual, activation) goes through a per-wave
+// fp32 LDS tile so that residual loads and output stores are 16 bytes per lane.  Blocks are
+// renumbered so that consecutive tiles (which share activation rows) run on the same XCD.
 // A launch is grouped: each block finds its problem (one per subnet cfg) from its tile number.
 #include "common.h"
 
@@ -26,35 +29,52 @@ namespace sna {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int BK = 64;             // reduction elements per LDS stage
-constexpr int LDS_STRIDE = 64;     // bf16 per LDS row: 128-byte rows, 16-byte chunks XOR-swizzled by (row >> 1) & 7
-constexpr int NTHREADS = 256;
-constexpr int TAP_TABLE = 40;      // entries per tap table (taps <= 32, rest zero)
-constexpr int SMEM_HEAD = 512;     // bytes reserved for the two tap tables
+constexpr int ROW_B = 128;         // bytes per LDS row (one K step of one tile row)
 
-template <int BM, int BN, int WARPS_M, int WARPS_N>
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
+// (vmcnt is split over bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait").
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+template <int BM, int BN, int WARPS_M, int WARPS_N, int NS>
 struct IgemmCfg {
+  static constexpr int NWAVES = WARPS_M * WARPS_N, NTHREADS = 64 * NWAVES;
   static constexpr int WTM = BM / WARPS_M, WTN = BN / WARPS_N;
   static constexpr int TM = WTM / 32, TN = WTN / 32;
-  static constexpr int EPI_STRIDE = WTN + 4;                                 // floats per staged row
-  static constexpr int TILE_BYTES = 2 * (BM + BN) * LDS_STRIDE * 2;
-  static constexpr int EPI_BYTES = 4 * 32 * EPI_STRIDE * 4;
-  static constexpr int SMEM = SMEM_HEAD + (TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES);
+  static constexpr int PASS_ROWS = NTHREADS / 8;                 // tile rows fetched per pass of the block
+  static constexpr int A_IT = (BM + PASS_ROWS - 1) / PASS_ROWS, B_IT = (BN + PASS_ROWS - 1) / PASS_ROWS;
+  static constexpr int STAGE_B = (BM + BN) * ROW_B;
+  static constexpr int EPI_STRIDE = WTN + 4;                     // floats per staged row
+  static constexpr int TILE_BYTES = NS * STAGE_B;
+  static constexpr int EPI_BYTES = NWAVES * 32 * EPI_STRIDE * 4;
+  static constexpr int SMEM = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, int WARPS_M, int WARPS_N>
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void igemm_kernel(const ConvGroupArgs args) {
-  using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N>;
-  static_assert(WARPS_M * WARPS_N == 4, "4 waves");
+__device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
+  u32x4 v;
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm));
+#else
+  v = u32x4{addr, (unsigned)imm, 0u, 0u};      // host pass only parses this file
+#endif
+  return v;
+}
+
+template <int BM, int BN, int WARPS_M, int WARPS_N, int NS>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const ConvGroupArgs args) {
+#if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
+  using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N, NS>;
   constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
   static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-  constexpr int A_IT = BM / 32, B_IT = BN / 32;      // rows fetched per thread (32 rows per pass)
+  static_assert(BM % 8 == 0 && BN % 8 == 0 && Cfg::PASS_ROWS % 8 == 0, "DMA rows come in groups of 8");
+  constexpr int A_IT = Cfg::A_IT, B_IT = Cfg::B_IT, L = A_IT + B_IT;   // DMA loads per thread per stage
+  static_assert((NS - 2) * L < 64, "vmcnt range");
+  static_assert(BM % Cfg::PASS_ROWS == 0 && BN % Cfg::PASS_ROWS == 0, "every wave issues the same number of loads");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  int* tap_x = (int*)smem;
-  int* tap_w = tap_x + TAP_TABLE;
-  bf16_t* tiles = (bf16_t*)(smem + SMEM_HEAD);
+  const unsigned lds0 = (unsigned)(size_t)(lds_char*)smem;              // LDS byte address of the tiles
 
   // XCD-aware renumbering: hardware block b runs on XCD b % 8; give each XCD a contiguous tile range
   const int per_xcd = gridDim.x >> 3;
@@ -70,37 +90,25 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WARPS_N, wn = wave % WARPS_N;
-  const int kc = tid & 7;                 // this thread's 16-byte unit inside a K step
-  const int lrow = tid >> 3;              // 0..31
+  const int lrow = tid >> 3;                               // row inside a pass
+  const int kc = (tid & 7) ^ ((lrow >> 1) & 7);            // global 16-byte unit this lane's LDS slot holds
 
-  const bf16_t* __restrict__ X = (const bf16_t*)p.x;
-  const bf16_t* __restrict__ Wt = (const bf16_t*)p.w;
   const int C = p.C, H = p.H, Wd = p.W, S = p.S, RS = p.R * p.S;
 
-  if (tid < TAP_TABLE) {
-    int tx = 0, tw = 0;
-    if (tid < RS) {
-      const int r = tid / S, s = tid - r * S;
-      tx = (r * Wd + s) * C;
-      tw = r * p.wr + s * p.ws;
-    }
-    tap_x[tid] = tx;
-    tap_w[tid] = tw;
-  }
-
-  // rows this thread fetches: base offset of the window's first tap and which taps are in range
+  // rows this thread fetches: byte offset of the window's first tap and which taps are in range
   int a_base[A_IT];
   unsigned a_mask[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
-    const int m = m0 + lrow + 32 * i;
+    const int row = lrow + Cfg::PASS_ROWS * i;
+    const int m = m0 + row;
     a_base[i] = 0;
     a_mask[i] = 0;
-    if (m < p.M) {
+    if (row < BM && m < p.M) {
       const int q = m % p.Wo, t = m / p.Wo;
       const int pp = t % p.Ho, n = t / p.Ho;
       const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
-      a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;       // bytes
+      a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;
       unsigned mk = 0;
       for (int r = 0; r < p.R; ++r)
         for (int s = 0; s < S; ++s)
@@ -112,53 +120,42 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
   unsigned b_ok = 0;
 #pragma unroll
   for (int j = 0; j < B_IT; ++j) {
-    const int k = n0 + lrow + 32 * j;
-    if (k < p.K) b_ok |= 1u << j;
-    b_base[j] = k * p.wk * 2;                             // bytes
+    const int row = lrow + Cfg::PASS_ROWS * j;
+    const int k = n0 + row;
+    if (row < BN && k < p.K) b_ok |= 1u << j;
+    b_base[j] = k * p.wk * 2;
   }
 
   // reduction position of this thread's unit: tap rs and channel octet c8
   int rs = kc / p.C8;
   int c8 = kc - rs * p.C8;
-
-  uint4 a_reg[2][A_IT], b_reg[2][B_IT];  // two K steps of operands in flight in registers
   const int KT = (p.K8 + 7) >> 3;         // K steps of 64 elements
-  __syncthreads();                        // tap tables visible
 
-  // Operand loads go through buffer descriptors: an offset at or beyond the tensor's size returns
-  // zeros without touching memory, which is how padding taps, ragged rows and the K tail are fed.
-  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)p.x_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, (int)p.w_bytes, 0x00020000);
   constexpr unsigned OOB = 0x80000000u;
-  auto fetch = [&](uint4 (&ar)[A_IT], uint4 (&br)[B_IT]) {
+  // LDS destination of this wave's DMA ops inside a stage: 64 lanes x 16 bytes = 8 consecutive rows
+  lds_char* const dma_a = (lds_char*)smem + (wave * 8) * ROW_B;
+  lds_char* const dma_b = dma_a + BM * ROW_B;
+
+  auto issue = [&](int stage) {
     const bool u_ok = rs < RS;
-    const int rsc = u_ok ? rs : RS;       // entry RS of the tables is zero
-    const int tx = (tap_x[rsc] + c8 * 8) * 2, tw = (tap_w[rsc] + c8 * 8) * 2;
+    const int r = (rs * p.inv_s) >> 16, s = rs - r * S;
+    const int tx = ((r * Wd + s) * C + c8 * 8) * 2, tw = (r * p.wr + s * p.ws + c8 * 8) * 2;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      const bool ok = u_ok && ((a_mask[i] >> rsc) & 1u);
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? (unsigned)(a_base[i] + tx) : OOB, 0, 0);
-      ar[i] = make_uint4(v.x, v.y, v.z, v.w);
+      const bool ok = u_ok && ((a_mask[i] >> (rs & 31)) & 1u);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dma_a + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * i * ROW_B, 16,
+                                               ok ? (unsigned)(a_base[i] + tx) : OOB, 0, 0, 0);
     }
 #pragma unroll
     for (int j = 0; j < B_IT; ++j) {
       const bool ok = u_ok && ((b_ok >> j) & 1u);
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, ok ? (unsigned)(b_base[j] + tw) : OOB, 0, 0);
-      br[j] = make_uint4(v.x, v.y, v.z, v.w);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, dma_b + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * j * ROW_B, 16,
+                                               ok ? (unsigned)(b_base[j] + tw) : OOB, 0, 0, 0);
     }
     c8 += 8;                              // advance one K step
     while (c8 >= p.C8) { c8 -= p.C8; ++rs; }
-  };
-  // LDS rows are 128 bytes (one K step); the 16-byte chunk c of row r lives in slot c ^ ((r >> 1) & 7),
-  // which keeps both the row-wise stores and the column-wise fragment loads free of bank conflicts.
-  const int kc_sw = kc ^ ((lrow >> 1) & 7);
-  auto stage = [&](int buf, const uint4 (&ar)[A_IT], const uint4 (&br)[B_IT]) {
-    bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE;
-    bf16_t* Bs = As + BM * LDS_STRIDE;
-#pragma unroll
-    for (int i = 0; i < A_IT; ++i) *(uint4*)(As + (lrow + 32 * i) * LDS_STRIDE + kc_sw * 8) = ar[i];
-#pragma unroll
-    for (int j = 0; j < B_IT; ++j) *(uint4*)(Bs + (lrow + 32 * j) * LDS_STRIDE + kc_sw * 8) = br[j];
   };
 
   f32x16 acc[TM][TN];
@@ -170,51 +167,59 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int frag_row = lane & 31, frag_hi = lane >> 5, frag_sw = (frag_row >> 1) & 7;
-  int frag_off[BK / 16];                   // swizzled element offset of this lane's chunk in each 16-wide slice
+  unsigned frag_off[BK / 16];              // swizzled byte offset of this lane's chunk in each 16-wide slice
 #pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) frag_off[ks] = ((ks * 2 + frag_hi) ^ frag_sw) * 8;
-  auto compute = [&](int buf) {
-    const bf16_t* As = tiles + buf * (BM + BN) * LDS_STRIDE + (wm * WTM + frag_row) * LDS_STRIDE;
-    const bf16_t* Bs = tiles + buf * (BM + BN) * LDS_STRIDE + (BM + wn * WTN + frag_row) * LDS_STRIDE;
-    bf16x8 af[2][TM], bfr[2][TN];        // fragments of the next 16-wide slice load while this one multiplies
+  for (int ks = 0; ks < BK / 16; ++ks) frag_off[ks] = (unsigned)(((ks * 2 + frag_hi) ^ frag_sw) * 16);
+  const unsigned a_lane = lds0 + (wm * WTM + frag_row) * ROW_B;
+  const unsigned b_lane = lds0 + (BM + wn * WTN + frag_row) * ROW_B;
+
+  auto compute = [&](int stage) {
+    const unsigned ab = a_lane + stage * Cfg::STAGE_B, bb = b_lane + stage * Cfg::STAGE_B;
+    u32x4 af[2][TM], bfr[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = *(const bf16x8*)(As + i * 32 * LDS_STRIDE + frag_off[0]);
+    for (int i = 0; i < TM; ++i) af[0][i] = lds_read_b128(ab + frag_off[0], i * 32 * ROW_B);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[0][j] = *(const bf16x8*)(Bs + j * 32 * LDS_STRIDE + frag_off[0]);
+    for (int j = 0; j < TN; ++j) bfr[0][j] = lds_read_b128(bb + frag_off[0], j * 32 * ROW_B);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
+      // fragments of slice ks were requested one slice ago: wait for them, then request slice ks+1
+      // before the MFMAs of slice ks so that the LDS latency runs under the matrix pipe
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[cur][i]));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bfr[cur][j]));
       if (ks + 1 < BK / 16) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[nxt][i] = *(const bf16x8*)(As + i * 32 * LDS_STRIDE + frag_off[ks + 1]);
+        for (int i = 0; i < TM; ++i) af[nxt][i] = lds_read_b128(ab + frag_off[ks + 1], i * 32 * ROW_B);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[nxt][j] = *(const bf16x8*)(Bs + j * 32 * LDS_STRIDE + frag_off[ks + 1]);
+        for (int j = 0; j < TN; ++j) bfr[nxt][j] = lds_read_b128(bb + frag_off[ks + 1], j * 32 * ROW_B);
       }
+      __builtin_amdgcn_sched_barrier(0);    // keep the requests ahead of the MFMAs that hide their latency
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[cur][i]),
+                                                              __builtin_bit_cast(bf16x8, bfr[cur][j]), acc[i][j], 0, 0, 0);
     }
   };
 
-  // Software pipeline.  At the top of step kt the register sets hold the operands of steps kt+1
-  // and kt+2 (loads in flight); set (kt+1)&1 goes to the idle LDS buffer and is refilled with
-  // step kt+3 before the MFMAs of step kt start, so LDS stores and global loads run under them.
-  fetch(a_reg[0], b_reg[0]);                        // step 0
-  stage(0, a_reg[0], b_reg[0]);
-  if (KT > 1) fetch(a_reg[1], b_reg[1]);            // step 1
-  if (KT > 2) fetch(a_reg[0], b_reg[0]);            // step 2
-  for (int kt = 0; kt < KT; kt += 2) {
-    __syncthreads();
-    if (kt + 1 < KT) stage(1, a_reg[1], b_reg[1]);
-    if (kt + 3 < KT) fetch(a_reg[1], b_reg[1]);
-    compute(0);
-    if (kt + 1 >= KT) break;
-    __syncthreads();
-    if (kt + 2 < KT) stage(0, a_reg[0], b_reg[0]);
-    if (kt + 4 < KT) fetch(a_reg[0], b_reg[0]);
-    compute(1);
+  // ---- main loop: ring of NS stages ----------------------------------------------------------
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+    if (st < KT) issue(st);
+  int stage = 0, fill = NS - 1;            // stage holding step kt; stage that step kt + NS - 1 goes to
+  for (int kt = 0; kt < KT; ++kt) {
+    // step kt's loads were issued NS-1 steps ago; up to NS-2 newer steps may stay in flight
+    if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();          // every wave's part of step kt is in LDS; step kt-1 fully consumed
+    if (kt + NS - 1 < KT) issue(fill);
+    compute(stage);
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
   }
   __syncthreads();
 
@@ -222,7 +227,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
   // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of a 32x32 tile.
   // Per 32-row strip: SubnetNorm scale/shift on the accumulators, fp32 strip into this wave's LDS
   // region, then each lane takes (row, 8 consecutive channels): residual, activation, store.
-  float* epi = (float*)(smem + SMEM_HEAD) + wave * 32 * Cfg::EPI_STRIDE;
+  float* epi = (float*)smem + wave * 32 * Cfg::EPI_STRIDE;
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
   float sc[TN], sh[TN];
 #pragma unroll
@@ -288,16 +293,18 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
         }
       }
     }
+    __builtin_amdgcn_wave_barrier();
   }
+#endif
 }
 
-struct Variant { int bm, bn, smem; void (*fn)(const ConvGroupArgs); };
-#define SNA_VARIANT(BM, BN, WM, WN) \
-  { BM, BN, IgemmCfg<BM, BN, WM, WN>::SMEM, igemm_kernel<BM, BN, WM, WN> }
+struct Variant { int bm, bn, threads, smem; void (*fn)(const ConvGroupArgs); };
+#define SNA_VARIANT(BM, BN, WM, WN, NS) \
+  { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, igemm_kernel<BM, BN, WM, WN, NS> }
 static const Variant kVariants[] = {
-    SNA_VARIANT(128, 128, 2, 2), SNA_VARIANT(128, 64, 2, 2), SNA_VARIANT(128, 96, 4, 1),
-    SNA_VARIANT(128, 32, 4, 1),  SNA_VARIANT(64, 64, 2, 2),  SNA_VARIANT(64, 128, 1, 4),
-    SNA_VARIANT(32, 128, 1, 4),
+    SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
+    SNA_VARIANT(128, 32, 4, 1, 4),  SNA_VARIANT(64, 64, 2, 2, 4),  SNA_VARIANT(64, 128, 1, 4, 3),
+    SNA_VARIANT(32, 128, 1, 4, 4),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -318,7 +325,7 @@ hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s) {
     attr_done[variant] = true;
   }
   const int blocks = (a.total_tiles + 7) / 8 * 8;
-  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(NTHREADS), v.smem, s, a);
+  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(v.threads), v.smem, s, a);
   return hipGetLastError();
 }
 
