@@ -185,6 +185,8 @@ def pack_weights(arch: ArchDesc, tensors: dict) -> np.ndarray:
         want = tuple(ti.dims[:nd])
         if a.shape != want:
             raise ValueError(f"{name}: shape {a.shape} != {want}")
+        if ti.kind == 0 and ti.c_pad > ti.dims[3]:          # stored input channels are zero-padded
+            a = np.concatenate([a, np.zeros(a.shape[:3] + (ti.c_pad - ti.dims[3],), np.float32)], axis=3)
         raw = _bf16_bits(a).tobytes() if ti.dtype == DTYPE["bf16"] else a.tobytes()
         assert len(raw) == ti.bytes, name
         blob[ti.offset:ti.offset + ti.bytes] = np.frombuffer(raw, dtype=np.uint8)

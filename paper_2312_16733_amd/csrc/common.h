@@ -49,6 +49,7 @@ struct ConvProblem {
   int y_stride;         // elements between output rows (>= K); lets a linear write a column block
   int res_stride;
   unsigned x_bytes, w_bytes;   // extent of x and of the active weight rows, for bounds-checked loads
+  int c_count;          // host bookkeeping: input channels that count as algorithmic work (0 = C)
   int res_after_act;    // 0: y = act(norm(conv) + res); 1: y = act(norm(conv)) + res
 };
 
@@ -107,6 +108,11 @@ struct CopyItem { unsigned long src, dst; unsigned long n; };   // byte offsets 
 #define SNA_COPY_ITEMS 128
 struct CopyArgs { const void* src; void* dst; int n; CopyItem it[SNA_COPY_ITEMS]; };
 
+// request inputs [pixels][c_in] bf16 -> [pixels][8] bf16, zero-padded channels (also gathers requests)
+struct PadItem { unsigned long src, dst; unsigned long pixels; };   // byte offsets
+#define SNA_PAD_ITEMS 128
+struct PadArgs { const void* src; void* dst; int n; int c_in; PadItem it[SNA_PAD_ITEMS]; };
+
 // ---- launchers (defined in the .hip files) ---------------------------------------------------
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s);
 void igemm_tile_shape(int variant, int* bm, int* bn);
@@ -119,6 +125,7 @@ hipError_t launch_se(const SeGroupArgs& a, hipStream_t s);
 hipError_t launch_layernorm(const LnGroupArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnGroupArgs& a, hipStream_t s);
 hipError_t launch_copy(const CopyArgs& a, hipStream_t s);
+hipError_t launch_pad_input(const PadArgs& a, hipStream_t s);
 hipError_t launch_fold_stats(const float* stats, float* folded, int n_subnets, long row_len, hipStream_t s);
 
 // ---- device helpers ---------------------------------------------------------------------------

@@ -165,7 +165,7 @@ struct Fwd {
     std::vector<int> var(ps.size());
     for (size_t i = 0; i < ps.size(); ++i) {
       const ConvProblem& q = ps[i];
-      if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 32) {
+      if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 64) {
         err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
         return;
       }
@@ -190,10 +190,11 @@ struct Fwd {
         p.tile_start = start;
         start += p.tiles;
         a.p[a.n++] = p;
-        const double mac = (double)p.M * p.K * p.C * p.R * p.S;
+        const int cc = p.c_count ? p.c_count : p.C;     // channel padding is not algorithmic work
+        const double mac = (double)p.M * p.K * cc * p.R * p.S;
         macs += (int64_t)mac;
         flops += 2 * mac;
-        bytes += 2.0 * ((double)p.N * p.H * p.W * p.C + (double)p.K * p.R * p.S * p.C) +
+        bytes += 2.0 * ((double)p.N * p.H * p.W * cc + (double)p.K * p.R * p.S * cc) +
                  (p.out_fp32 ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K + (p.res ? 2.0 * p.M * p.K : 0.0);
       }
       a.total_tiles = start;
@@ -339,6 +340,31 @@ struct Fwd {
     if (!items.empty()) copy_items(inputs, net->arena, items);
   }
 
+  // bf16 image families: every group's requests are copied into its input buffer with the
+  // channels padded to 8 (which also gathers scattered requests), so the stem runs on MFMA.
+  void pad_inputs(const void* inputs, const std::vector<size_t>& req_off) {
+    const int c_in = T().arch.in_ch;
+    std::vector<PadItem> items;
+    for (Group& g : groups) {
+      const size_t pix = (size_t)g.cfg->in_h * g.cfg->in_w;
+      size_t d = (size_t)(g.inbuf - net->arena);
+      if (g.contiguous) {
+        items.push_back({req_off[g.reqs[0]], d, pix * g.n});
+      } else {
+        for (int r : g.reqs) { items.push_back({req_off[r], d, pix}); d += pix * 16; }
+      }
+      g.cur = g.inbuf;
+    }
+    for (size_t i = 0; i < items.size(); i += SNA_PAD_ITEMS) {
+      PadArgs a;
+      a.src = inputs; a.dst = net->arena; a.c_in = c_in;
+      a.n = (int)std::min<size_t>(SNA_PAD_ITEMS, items.size() - i);
+      double bytes = 0;
+      for (int j = 0; j < a.n; ++j) { a.it[j] = items[i + j]; bytes += (2.0 * c_in + 16.0) * items[i + j].pixels; }
+      launch(KC_COPY, 0, bytes, [&] { return launch_pad_input(a, stream); });
+    }
+  }
+
   // The head writes logits straight to the caller's buffer for contiguous groups, else into
   // the group's scratch; scatter_logits() then moves rows to request order.
   float* logits_target(Group& g, float* logits) {
@@ -408,10 +434,11 @@ sna_status Fwd::run_tiny(const void*, float* logits) {
 // ------------------------------------------------------------------------------------------
 sna_status Fwd::run_resnet(const void*, float* logits) {
   const sna_arch_desc& a = T().arch;
-  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = a.in_ch; }
-  conv_slot(true, [&](Group& g, ConvProblem& p) {
+  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = 8; }     // channel-padded inputs
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
     p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
     slice_conv(p, tensor("stem.w"), g.cfg->stage_out_ch[0], 7, 2);
+    p.c_count = a.in_ch;
     p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
     p.act = SNA_ACT_RELU; p.y = g.buf[0];
     g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
@@ -490,13 +517,14 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
 // ------------------------------------------------------------------------------------------
 sna_status Fwd::run_mbv3(const void*, float* logits) {
   const sna_arch_desc& a = T().arch;
-  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = a.in_ch; }
+  for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = 8; }     // channel-padded inputs
   auto sn = [&](ConvProblem& p, const std::string& name, const Group& g) {
     p.scale = scale_of(name, g.cfg->subnet_id); p.shift = shift_of(name, g.cfg->subnet_id);
   };
-  conv_slot(true, [&](Group& g, ConvProblem& p) {
+  conv_slot(false, [&](Group& g, ConvProblem& p) {
     p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
     slice_conv(p, tensor("stem.w"), a.stem_ch, 3, 2);
+    p.c_count = a.in_ch;
     sn(p, "stem.sn", g);
     p.act = SNA_ACT_HSWISH; p.y = g.buf[0];
     g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
@@ -884,7 +912,8 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   if ((size_t)(cur - net->arena) > net->arena_bytes) return fail(SNA_E_WORKSPACE, "arena overflow");
 
   if (net->prof_on && net->prof_recs.size() > 200000) return fail(SNA_E_BATCH, "profile buffer full: call sna_profile_read");
-  f.bind_inputs(inputs_dev, req_off, req_bytes);
+  if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3) f.pad_inputs(inputs_dev, req_off);
+  else f.bind_inputs(inputs_dev, req_off, req_bytes);
   sna_status st;
   switch (a.family) {
     case SNA_FAMILY_TINY: st = f.run_tiny(inputs_dev, logits_dev); break;

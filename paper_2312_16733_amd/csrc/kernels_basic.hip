@@ -256,6 +256,34 @@ hipError_t launch_copy(const CopyArgs& a, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Channel padding of request inputs: [pixels][c_in] bf16 -> [pixels][8] bf16 with zeros in the
+// added channels, so that a narrow-input stem conv can use 16-byte operand loads on the MFMA
+// path.  Block (b, y) handles a share of item b; one thread = one pixel (16-byte store).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pad_input_kernel(const PadArgs args) {
+  const PadItem it = args.it[blockIdx.x];
+  const bf16_t* s = (const bf16_t*)((const char*)args.src + it.src);
+  uint4* d = (uint4*)((char*)args.dst + it.dst);
+  const int c = args.c_in;
+  for (unsigned long i = blockIdx.y * 256 + threadIdx.x; i < it.pixels; i += (unsigned long)gridDim.y * 256) {
+    unsigned v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = e < c ? (unsigned)s[i * c + e] : 0u;
+    d[i] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+  }
+}
+
+hipError_t launch_pad_input(const PadArgs& a, hipStream_t s) {
+  if (a.n == 0) return hipSuccess;
+  unsigned long mx = 0;
+  for (int i = 0; i < a.n; ++i) mx = a.it[i].pixels > mx ? a.it[i].pixels : mx;
+  long gy = (long)((mx + 256 * 4 - 1) / (256 * 4));
+  gy = gy < 1 ? 1 : (gy > 2048 ? 2048 : gy);
+  hipLaunchKernelGGL(pad_input_kernel, dim3(a.n, (unsigned)gy), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // SubnetNorm folding at load time: stats [n_subnets][4][row_len] (mean, var, gamma, beta) ->
 // folded [n_subnets][2][row_len] with scale = gamma / sqrt(var + eps), shift = beta - mean*scale.
 // ---------------------------------------------------------------------------------------------

@@ -32,6 +32,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int BK = 64;             // reduction elements per LDS stage
+static_assert(BK == 64, "one LDS row holds one K step");
 constexpr int ROW_B = 128;         // bytes per LDS row (one K step of one tile row)
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
 
   // rows this thread fetches: byte offset of the window's first tap and which taps are in range
   int a_base[A_IT];
-  unsigned a_mask[A_IT];
+  unsigned long long a_mask[A_IT];      // bit rs set: tap rs of this row's window is inside the image
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
     const int row = lrow + Cfg::PASS_ROWS * i;
@@ -109,10 +110,10 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
       const int pp = t % p.Ho, n = t / p.Ho;
       const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
       a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;
-      unsigned mk = 0;
+      unsigned long long mk = 0;
       for (int r = 0; r < p.R; ++r)
         for (int s = 0; s < S; ++s)
-          if (ih0 + r >= 0 && ih0 + r < H && iw0 + s >= 0 && iw0 + s < Wd) mk |= 1u << (r * S + s);
+          if (ih0 + r >= 0 && ih0 + r < H && iw0 + s >= 0 && iw0 + s < Wd) mk |= 1ull << (r * S + s);
       a_mask[i] = mk;
     }
   }
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
     const int tx = ((r * Wd + s) * C + c8 * 8) * 2, tw = (r * p.wr + s * p.ws + c8 * 8) * 2;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      const bool ok = u_ok && ((a_mask[i] >> (rs & 31)) & 1u);
+      const bool ok = u_ok && ((a_mask[i] >> (rs & 63)) & 1ull);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dma_a + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * i * ROW_B, 16,
                                                ok ? (unsigned)(a_base[i] + tx) : OOB, 0, 0, 0);
     }

@@ -32,7 +32,10 @@ struct Builder {
     ti.dtype = dtype;
     ti.dims[0] = d0; ti.dims[1] = d1; ti.dims[2] = d2; ti.dims[3] = d3;
     ti.c_pad = kind == 0 ? d3 : (kind == 1 ? d2 : (kind == 2 ? d1 : d0));
-    const int64_t elems = (int64_t)d0 * d1 * d2 * d3;
+    // conv weights of a bf16 family store their input channels padded to a multiple of 8 (zeros),
+    // so that a 3-channel stem runs on the MFMA path over channel-padded inputs
+    if (kind == 0 && dtype == SNA_DTYPE_BF16) ti.c_pad = (d3 + 7) / 8 * 8;
+    const int64_t elems = kind == 0 ? (int64_t)d0 * d1 * d2 * ti.c_pad : (int64_t)d0 * d1 * d2 * d3;
     ti.bytes = elems * (dtype == SNA_DTYPE_BF16 ? 2 : 4);
     ti.offset = off;
     off += (ti.bytes + 255) / 256 * 256;
@@ -104,7 +107,7 @@ sna_status build_tables(const sna_arch_desc* a, ArchTables* t) {
     }
     b.linear("head.w", a->n_classes, prev);
     b.vec("head.b", a->n_classes);
-    t->in_elems_max = (int64_t)a->max_res * a->max_res * a->in_ch;
+    t->in_elems_max = (int64_t)a->max_res * a->max_res * (a->dtype == SNA_DTYPE_BF16 ? 8 : a->in_ch);
     t->small_elems = prev + a->n_classes;
   } else if (fam == SNA_FAMILY_RESNET) {
     if (a->dtype != SNA_DTYPE_BF16) return fail(SNA_E_ARCH, "RESNET family is bf16");
@@ -131,7 +134,7 @@ sna_status build_tables(const sna_arch_desc* a, ArchTables* t) {
     }
     b.linear("head.w", a->n_classes, prev);
     b.vec("head.b", a->n_classes);
-    t->in_elems_max = (int64_t)a->max_res * a->max_res * a->in_ch;
+    t->in_elems_max = (int64_t)a->max_res * a->max_res * (a->dtype == SNA_DTYPE_BF16 ? 8 : a->in_ch);
     t->small_elems = prev + a->n_classes;
   } else if (fam == SNA_FAMILY_MBV3) {
     if (a->dtype != SNA_DTYPE_BF16) return fail(SNA_E_ARCH, "MBV3 family is bf16");
@@ -167,7 +170,7 @@ sna_status build_tables(const sna_arch_desc* a, ArchTables* t) {
     upd((int64_t)h * h * a->tail_ch);
     b.linear("fc1.w", a->fc_ch, a->tail_ch); b.vec("fc1.b", a->fc_ch);
     b.linear("head.w", a->n_classes, a->fc_ch); b.vec("head.b", a->n_classes);
-    t->in_elems_max = (int64_t)a->max_res * a->max_res * a->in_ch;
+    t->in_elems_max = (int64_t)a->max_res * a->max_res * (a->dtype == SNA_DTYPE_BF16 ? 8 : a->in_ch);
     const int64_t head_small = (int64_t)a->tail_ch + a->fc_ch + a->n_classes;
     t->small_elems = small > head_small ? small : head_small;
   } else if (fam == SNA_FAMILY_TRANSFORMER) {
