@@ -17,6 +17,18 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+def stored_traffic():
+    """HBM bytes per igemm launch from the committed rocprofv3 counter summary (not measurable live)."""
+    path = os.path.join(ROOT, "profiles", "igemm_resnet_b64_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("bytes_per_launch"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
@@ -54,6 +66,9 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy 4 times (reference reading for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; the path shards by request across "
@@ -89,6 +104,13 @@ def main():
         ci = i % n_cfgs
         net.forward(cfgs_c[ci], r[:batch], inputs[C[ci].in_h], logits=logits)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -115,7 +137,9 @@ def main():
                    "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0}
                for k, v in prof.items()}
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(),
+                "algorithmic_bytes_per_launch": ig["bytes"] / max(ig["launches"], 1),
+                "frac_of_hbm_peak": (ig["bytes"] / (ig["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS) if ig["ms"] > 0 else 0.0,
                 "kernel": "igemm_kernel (all tile variants)",
                 "avg_launch_us": 1e3 * ig["ms"] / max(ig["launches"], 1),
                 "launches": ig["launches"],
