@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--family", default="resnet", choices=["resnet", "mbv3", "transformer"],
+                    help="resnet = the headline workload (BASELINE config 2); the others are extra reports")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -85,20 +87,23 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(3)
     dev = torch.device("cuda:0")
-    spec = synth.ResNetSpec()
-    n_cfgs, B = 16, args.batch
+    spec = {"resnet": synth.ResNetSpec, "mbv3": synth.MBV3Spec, "transformer": synth.TransformerSpec}[args.family]()
+    n_cfgs, B = (12 if args.family == "transformer" else 16), args.batch
+    if args.family == "transformer":
+        B = min(B, 32)
     W = synth.make_weights(spec, 2312)
     S = synth.make_stats(spec, n_cfgs, 2312)
     C = synth.enumerate_cfgs(spec, n_cfgs, 16733)
-    net = sna.Supernet(spec, W, S, n_cfgs, max(B, 64))
+    MB = max(B, 64) if args.family != "transformer" else 32
+    net = sna.Supernet(spec, W, S, n_cfgs, MB)
     cfgs_c = [net.prepare_cfgs([c]) for c in C]
-    route = np.zeros(B, np.int32)
+    route = np.zeros(MB, np.int32)
     inputs = {}
     for c in C:
         if c.in_h not in inputs:
-            inputs[c.in_h] = torch.from_numpy(synth.make_inputs(spec, max(B, 64), c.in_h, c.in_w, 5)) \
+            inputs[c.in_h] = torch.from_numpy(synth.make_inputs(spec, MB, c.in_h, c.in_w, 5)) \
                 .to(torch.bfloat16).to(dev)
-    logits = torch.empty((max(B, 64), spec.n_classes), dtype=torch.float32, device=dev)
+    logits = torch.empty((MB, spec.n_classes), dtype=torch.float32, device=dev)
 
     def step(i, batch=B, r=route):
         ci = i % n_cfgs
@@ -149,7 +154,7 @@ def main():
     detail = None
     if not args.no_detail:
         detail = {}
-        for b in (1, 16, 64):
+        for b in ((1, 16, 64) if args.family != "transformer" else (1, 8, 32)):
             for tag, ci in (("min", 0), ("median", n_cfgs // 2), ("max", n_cfgs - 1)):
                 for i in range(3):
                     step(ci, b)
@@ -167,8 +172,12 @@ def main():
            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": "ResNet-50-shaped elastic SuperNet (BASELINE config 2), bf16, "
-                                  f"batch {B}, 16 seeded subnet cfgs walked smallest to largest, one cfg per step",
+           "config": {"workload": {"resnet": "ResNet-50-shaped elastic SuperNet (BASELINE config 2)",
+                                   "mbv3": "MobileNetV3-shaped elastic SuperNet (BASELINE config 3)",
+                                   "transformer": "elastic-width Transformer SuperNet (BASELINE config 5), "
+                                                  "requests of 128 tokens"}[args.family] +
+                                  f", bf16, batch {B}, {n_cfgs} seeded subnet cfgs walked smallest to largest, "
+                                  "one cfg per step",
                       "batch": B, "n_cfgs": n_cfgs,
                       "gmacs_per_image_range": [synth.subnet_macs(spec, C[0]) / 1e9,
                                                 synth.subnet_macs(spec, C[-1]) / 1e9],

@@ -84,6 +84,7 @@ struct SeProblem {
   const void* w2; const float* b2;  // [C_max][Q_max]
   float* pooled;        // [N][C] scratch
   float* gate;          // [N][C] scratch
+  float* hidden;        // [N][Q] scratch
   int N, HW, C, Q;
   int w1_stride, w2_stride;
   int tile_start, tiles;

@@ -583,7 +583,7 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
           p.x = g.buf[3]; p.y = g.buf[3];
           p.w1 = wptr(t1); p.b1 = (const float*)wptr(tensor(pre + "se.fc1.b")); p.w1_stride = t1.dims[1];
           p.w2 = wptr(t2); p.b2 = (const float*)wptr(tensor(pre + "se.fc2.b")); p.w2_stride = t2.dims[1];
-          p.pooled = g.small; p.gate = g.small + (size_t)g.n * m;
+          p.pooled = g.small; p.gate = g.small + (size_t)g.n * m; p.hidden = g.small + (size_t)2 * g.n * m;
           p.N = g.n; p.HW = out_size(g.H, 3, st) * out_size(g.W, 3, st); p.C = m; p.Q = g.cfg->block_aux_ch[s][j];
           return true;
         });

@@ -59,23 +59,21 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) 
   for (int r = 0; r < K; ++r) {
     const int ih = pp * STRIDE + r - PAD;
     if (ih < 0 || ih >= p.H) continue;
-    uint4 col[COLS];
+    float col[COLS][8];                   // this kernel row's input columns, converted once
 #pragma unroll
     for (int cidx = 0; cidx < COLS; ++cidx) {
       const int iw = iw0 + cidx;
-      col[cidx] = (iw >= 0 && iw < p.W) ? *(const uint4*)(x + ((long)ih * p.W + iw) * p.C) : make_uint4(0, 0, 0, 0);
+      const uint4 v = (iw >= 0 && iw < p.W) ? *(const uint4*)(x + ((long)ih * p.W + iw) * p.C) : make_uint4(0, 0, 0, 0);
+      unpack8(v, col[cidx]);
     }
 #pragma unroll
     for (int s = 0; s < K; ++s) {
       float wv[8];
       unpack8(*(const uint4*)(w + (long)r * p.wr + (long)s * p.ws), wv);
 #pragma unroll
-      for (int o = 0; o < DW_TW; ++o) {
-        float xv[8];
-        unpack8(col[o * STRIDE + s], xv);
+      for (int o = 0; o < DW_TW; ++o)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(xv[e], wv[e], acc[o][e]);
-      }
+        for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(col[o * STRIDE + s][e], wv[e], acc[o][e]);
     }
   }
   float sc[8], sh[8];
@@ -119,11 +117,9 @@ hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Squeeze-excite gate, one block per request:
+// Squeeze-excite gate:
 //   z = pooled[n][:C] (fp32 mean over pixels, computed by the pooling kernel)
 //   h = relu(W1[:Q,:C] z + b1[:Q]);  gate = hardsigmoid(W2[:C,:Q] h + b2[:C])
-// A wave owns an output and strides over the reduction with 64 lanes, then reduces in a fixed
-// butterfly order.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -131,29 +127,41 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-__global__ __launch_bounds__(256) void se_gate_kernel(const SeGroupArgs args) {
-  __shared__ float zs[1024];
-  __shared__ float hs[256];
+// One fully-connected layer of the gate: out[n][o] = f(W[o, :I] . in[n][:I] + b[o]) for o < O.
+// A block owns one request and 32 outputs; each of its 4 waves computes 8 of them, one at a
+// time: lanes read 8 consecutive bf16 weights (16 bytes) and the matching fp32 inputs, then the
+// wave reduces in a fixed butterfly order.  HSIG selects hard-sigmoid (second layer) or ReLU.
+template <bool HSIG>
+__global__ __launch_bounds__(256) void se_fc_kernel(const SeGroupArgs args) {
   const int g = find_problem(args, blockIdx.x);
   const SeProblem& p = args.p[g];
-  const int n = blockIdx.x - p.tile_start;
+  const int I = HSIG ? p.Q : p.C, O = HSIG ? p.C : p.Q;
+  const int oblocks = (O + 31) / 32;
+  const int local = blockIdx.x - p.tile_start;
+  const int n = local / oblocks, ob = local % oblocks;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int c = threadIdx.x; c < p.C; c += 256) zs[c] = p.pooled[(long)n * p.C + c];
-  __syncthreads();
-  const bf16_t* w1 = (const bf16_t*)p.w1;
-  for (int q = wave; q < p.Q; q += 4) {
+  const bf16_t* w = (const bf16_t*)(HSIG ? p.w2 : p.w1);
+  const int ws = HSIG ? p.w2_stride : p.w1_stride;
+  const float* bias = HSIG ? p.b2 : p.b1;
+  const float* in = (HSIG ? p.hidden : p.pooled) + (long)n * I;
+  float* out = (HSIG ? p.gate : p.hidden) + (long)n * O;
+#pragma unroll 1
+  for (int t = 0; t < 8; ++t) {
+    const int o = ob * 32 + wave * 8 + t;
+    if (o >= O) break;
     float a = 0.f;
-    for (int c = lane; c < p.C; c += 64) a = fmaf(bf16_to_f32(w1[(long)q * p.w1_stride + c]), zs[c], a);
+    for (int i8 = lane; i8 < (I >> 3); i8 += 64) {
+      float wv[8];
+      unpack8(*(const uint4*)(w + (long)o * ws + i8 * 8), wv);
+      const float4 x0 = *(const float4*)(in + i8 * 8), x1 = *(const float4*)(in + i8 * 8 + 4);
+      a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
+      a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
+    }
     a = wave_sum(a);
-    if (lane == 0) hs[q] = fmaxf(a + p.b1[q], 0.f);
-  }
-  __syncthreads();
-  const bf16_t* w2 = (const bf16_t*)p.w2;
-  for (int c = wave; c < p.C; c += 4) {
-    float a = 0.f;
-    for (int q = lane; q < p.Q; q += 64) a = fmaf(bf16_to_f32(w2[(long)c * p.w2_stride + q]), hs[q], a);
-    a = wave_sum(a);
-    if (lane == 0) p.gate[(long)n * p.C + c] = fminf(fmaxf(a + p.b2[c] + 3.f, 0.f), 6.f) * (1.f / 6.f);
+    if (lane == 0) {
+      a += bias[o];
+      out[o] = HSIG ? fminf(fmaxf(a + 3.f, 0.f), 6.f) * (1.f / 6.f) : fmaxf(a, 0.f);
+    }
   }
 }
 
@@ -181,11 +189,20 @@ hipError_t launch_se(const SeGroupArgs& a, hipStream_t s) {
   SeGroupArgs b = a;
   int start = 0;
   for (int i = 0; i < b.n; ++i) {
-    if (b.p[i].C > 1024 || b.p[i].Q > 256) return hipErrorInvalidValue;
-    b.p[i].tile_start = start; b.p[i].tiles = b.p[i].N; start += b.p[i].N;
+    if (b.p[i].C % 8 || b.p[i].Q % 8 || b.p[i].w1_stride % 8 || b.p[i].w2_stride % 8) return hipErrorInvalidValue;
+    b.p[i].tiles = b.p[i].N * ((b.p[i].Q + 31) / 32);
+    b.p[i].tile_start = start; start += b.p[i].tiles;
   }
-  hipLaunchKernelGGL(se_gate_kernel, dim3(start), dim3(256), 0, s, b);
+  hipLaunchKernelGGL(se_fc_kernel<false>, dim3(start), dim3(256), 0, s, b);
   hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  start = 0;
+  for (int i = 0; i < b.n; ++i) {
+    b.p[i].tiles = b.p[i].N * ((b.p[i].C + 31) / 32);
+    b.p[i].tile_start = start; start += b.p[i].tiles;
+  }
+  hipLaunchKernelGGL(se_fc_kernel<true>, dim3(start), dim3(256), 0, s, b);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   start = 0;
   for (int i = 0; i < b.n; ++i) {
