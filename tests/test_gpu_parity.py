@@ -344,3 +344,70 @@ def test_transformer_short_sequences(torch_mod):
         say("short tf cfg", c.subnet_id, "rel err %.3e" % e)
         assert np.abs(hid - ref_hid).max() <= 2e-2 * np.abs(ref_hid).max()
     net.close()
+
+
+# ------------------------------------------------------------------ edge cases
+def test_head_width_not_multiple_of_8(torch_mod):
+    """n_classes = 10 on a bf16 family: the head leaves the MFMA path (rows of 10 floats are not
+    16-byte granular) and runs on the direct kernel; logits rows are scattered with 2-byte copies."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.ResNetSpec(n_classes=10, stem_ch=16, stage_ch=(32, 64, 96, 128),
+                            max_depth=(3, 3, 4, 3), res_choices=(33, 48))
+    W, S, C = setup(spec, 6)
+    net = sna.Supernet(spec, W, S, 6, 8)
+    route = np.array([2, 5, 2, 0, 5], dtype=np.int32)
+    xs = [synth.make_inputs(spec, 1, C[ci].in_h, C[ci].in_w, 400 + r) for r, ci in enumerate(route)]
+    flat = np.concatenate([a.ravel() for a in xs])
+    got = net.forward(C, route, to_dev(torch, spec, flat))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for r, ci in enumerate(route):
+        check_parity(got[r:r + 1], oracle.forward(spec, W, S, C[ci], xs[r]), "bf16", f"req {r} cfg {ci}")
+    net.close()
+
+
+def test_sixteen_groups_and_too_many(torch_mod):
+    """16 distinct cfgs in one call is the grouped-launch limit; a 17th is refused before any launch."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.TinySpec()
+    W, S, C = setup(spec, 20)
+    net = sna.Supernet(spec, W, S, 20, 32)
+    x = synth.make_inputs(spec, 17, 32, 32, 41)
+    route = np.arange(16, dtype=np.int32)
+    got = net.forward(C, route, to_dev(torch, spec, x[:16]))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for r in range(16):
+        check_parity(got[r:r + 1], oracle.forward(spec, W, S, C[r], x[r:r + 1]), "fp32", f"tiny req {r}")
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward(C, np.arange(17, dtype=np.int32), to_dev(torch, spec, x))
+    assert ei.value.status == -6
+    net.close()
+
+
+def test_max_batch_boundary_and_workspace_check(torch_mod):
+    import ctypes
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.TinySpec()
+    W, S, C = setup(spec, 8)
+    net = sna.Supernet(spec, W, S, 8, 4)
+    x = to_dev(torch, spec, synth.make_inputs(spec, 5, 32, 32, 42))
+    out = net.forward([C[3]], [0] * 4, x)            # exactly max_batch
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(out.cpu().numpy()))
+    with pytest.raises(sna.SnaError) as ei:
+        net.forward([C[3]], [0] * 5, x)
+    assert ei.value.status == -6
+    # a workspace one byte short is refused at load
+    ws = sna.lib().sna_workspace_bytes(ctypes.byref(net.arch), 8, 4)
+    small = torch.empty(ws - 256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(sna.SnaError) as ei:
+        sna.supernet_load(net.arch, net.weights.data_ptr(), net.weights.numel(), net.stats.data_ptr(),
+                          net.stats.numel() * 4, 8, 4, small.data_ptr(), small.numel(), 0)
+    assert ei.value.status == -7
+    net.close()
