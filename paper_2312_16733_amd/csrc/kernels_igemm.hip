@@ -83,7 +83,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
   if (tile_id >= args.total_tiles) return;
 
   const int g = find_problem(args, tile_id);
-  const ConvProblem& p = args.p[g];
+  const ConvProblem p = args.p[g];         // by value: uniform fields live in SGPRs across the asm blocks
   const int local = tile_id - p.tile_start;
   const int tn = local % p.tiles_n, tm = local / p.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
