@@ -40,7 +40,7 @@ struct ConvProblem {
   int wk, wr, ws;       // element strides of the stored weight tensor (c stride = 1)
   int M;                // N*Ho*Wo
   int C8, K8;           // C/8, R*S*C/8 (igemm only)
-  unsigned magic_c8;    // ceil(2^24 / C8)
+  unsigned magic_wo, magic_ho;   // floor(2^32 / d) + 1 for d = Wo, Ho (0 when d == 1): x / d = mulhi(x, magic) while x * d < 2^32
   int inv_s;            // ceil(2^16 / S): tap row r = (rs * inv_s) >> 16
   int tiles_n;          // tiles along K (igemm)
   int tile_start, tiles;

@@ -131,7 +131,9 @@ struct Fwd {
     p.Ho = out_size(p.H, ksize, stride); p.Wo = out_size(p.W, ksize, stride);
     p.M = p.N * p.Ho * p.Wo;
     p.C8 = p.C / 8; p.K8 = p.R * p.S * p.C8;
-    p.magic_c8 = p.C8 > 0 ? (unsigned)(((1u << 24) + p.C8 - 1) / p.C8) : 0;
+    p.magic_wo = p.Wo > 1 ? (unsigned)((1ull << 32) / (unsigned)p.Wo + 1) : 0;
+    p.magic_ho = p.Ho > 1 ? (unsigned)((1ull << 32) / (unsigned)p.Ho + 1) : 0;
+    if ((double)p.M * (p.Wo > p.Ho ? p.Wo : p.Ho) >= 4294967296.0) err = hipErrorInvalidValue;   // reciprocal range
     p.inv_s = (65536 + p.S - 1) / p.S;
     p.y_stride = K; p.res_stride = K;
     const int esize = ti.dtype == SNA_DTYPE_BF16 ? 2 : 4;

@@ -99,6 +99,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
   // rows this thread fetches: byte offset of the window's first tap and which taps are in range
   int a_base[A_IT];
   unsigned long long a_mask[A_IT];      // bit rs set: tap rs of this row's window is inside the image
+  const bool pointwise = RS == 1 && p.stride == 1 && p.pad == 0;   // output pixel m reads input pixel m
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
     const int row = lrow + Cfg::PASS_ROWS * i;
@@ -106,15 +107,25 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
     a_base[i] = 0;
     a_mask[i] = 0;
     if (row < BM && m < p.M) {
-      const int q = m % p.Wo, t = m / p.Wo;
-      const int pp = t % p.Ho, n = t / p.Ho;
-      const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
-      a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;
-      unsigned long long mk = 0;
-      for (int r = 0; r < p.R; ++r)
+      if (pointwise) {
+        a_base[i] = m * C * 2;
+        a_mask[i] = 1;
+      } else {
+        // m -> (n, pp, q) with multiply-high by the host's reciprocals (exact for m * divisor < 2^32)
+        const int t = p.Wo == 1 ? m : (int)__umulhi((unsigned)m, p.magic_wo);
+        const int q = m - t * p.Wo;
+        const int n = p.Ho == 1 ? t : (int)__umulhi((unsigned)t, p.magic_ho);
+        const int pp = t - n * p.Ho;
+        const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
+        a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;
+        unsigned colm = 0;                // taps of one window row that fall inside the image
         for (int s = 0; s < S; ++s)
-          if (ih0 + r >= 0 && ih0 + r < H && iw0 + s >= 0 && iw0 + s < Wd) mk |= 1ull << (r * S + s);
-      a_mask[i] = mk;
+          if (iw0 + s >= 0 && iw0 + s < Wd) colm |= 1u << s;
+        unsigned long long mk = 0;
+        for (int r = 0; r < p.R; ++r)
+          if (ih0 + r >= 0 && ih0 + r < H) mk |= (unsigned long long)colm << (r * S);
+        a_mask[i] = mk;
+      }
     }
   }
   int b_base[B_IT];
@@ -211,6 +222,18 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st)
     if (st < KT) issue(st);
+
+  // SubnetNorm scale / shift of this lane's output columns, requested behind the first stages' loads so
+  // that they arrive under the main loop
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  float sc[TN], sh[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int k = n0 + wn * WTN + j * 32 + col_l;
+    sc[j] = (p.scale && k < p.K) ? p.scale[k] : 1.f;
+    sh[j] = (p.shift && k < p.K) ? p.shift[k] : 0.f;
+  }
+
   int stage = 0, fill = NS - 1;            // stage holding step kt; stage that step kt + NS - 1 goes to
   for (int kt = 0; kt < KT; ++kt) {
     // step kt's loads were issued NS-1 steps ago; up to NS-2 newer steps may stay in flight
@@ -229,14 +252,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
   // Per 32-row strip: SubnetNorm scale/shift on the accumulators, fp32 strip into this wave's LDS
   // region, then each lane takes (row, 8 consecutive channels): residual, activation, store.
   float* epi = (float*)smem + wave * 32 * Cfg::EPI_STRIDE;
-  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-  float sc[TN], sh[TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int k = n0 + wn * WTN + j * 32 + col_l;
-    sc[j] = (p.scale && k < p.K) ? p.scale[k] : 1.f;
-    sh[j] = (p.shift && k < p.K) ? p.shift[k] : 0.f;
-  }
   constexpr int OCT = WTN / 8;                 // channel octets per staged row
   constexpr int PAIRS = 32 * OCT / 64;         // (row, octet) pairs per lane
 #pragma unroll
@@ -299,9 +314,10 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
 #endif
 }
 
-struct Variant { int bm, bn, threads, smem; void (*fn)(const ConvGroupArgs); };
+struct Variant { int bm, bn, threads, smem, ns, stage_bytes, epi_bytes; void (*fn)(const ConvGroupArgs); };
 #define SNA_VARIANT(BM, BN, WM, WN, NS) \
-  { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, igemm_kernel<BM, BN, WM, WN, NS> }
+  { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS> }
 static const Variant kVariants[] = {
     SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
     SNA_VARIANT(128, 32, 4, 1, 4),  SNA_VARIANT(64, 64, 2, 2, 4),  SNA_VARIANT(64, 128, 1, 4, 3),
@@ -325,8 +341,17 @@ hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done[variant] = true;
   }
+  // a launch whose problems all have fewer K steps than the ring has stages only touches the
+  // leading stages: asking for less LDS lets more blocks share a CU
+  int kt_max = 1;
+  for (int i = 0; i < a.n; ++i) {
+    const int kt = (a.p[i].K8 + 7) >> 3;
+    if (kt > kt_max) kt_max = kt;
+  }
+  const int stages = kt_max < v.ns ? kt_max : v.ns;
+  const int smem = stages * v.stage_bytes > v.epi_bytes ? stages * v.stage_bytes : v.epi_bytes;
   const int blocks = (a.total_tiles + 7) / 8 * 8;
-  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(v.threads), v.smem, s, a);
+  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(v.threads), smem, s, a);
   return hipGetLastError();
 }
 
