@@ -167,7 +167,8 @@ struct Fwd {
     std::vector<int> var(ps.size());
     for (size_t i = 0; i < ps.size(); ++i) {
       const ConvProblem& q = ps[i];
-      if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 64) {
+      if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 64 ||
+          (q.out_fp32 && (q.act != SNA_ACT_NONE || q.res))) {
         err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
         return;
       }

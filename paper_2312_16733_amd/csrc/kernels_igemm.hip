@@ -24,6 +24,8 @@
 // A launch is grouped: each block finds its problem (one per subnet cfg) from its tile number.
 #include "common.h"
 
+#include <type_traits>
+
 namespace sna {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -63,8 +65,12 @@ __device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
   return v;
 }
 
+// Waves per SIMD the register allocation must leave room for: tiles with short reductions are
+// launched with a small LDS request and then run that many blocks per CU.
+constexpr int igemm_min_waves(int bm, int bn) { return bm * bn >= 128 * 128 ? 3 : (bm * bn >= 128 * 96 ? 4 : 5); }
+
 template <int BM, int BN, int WARPS_M, int WARPS_N, int NS>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const ConvGroupArgs args) {
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) void igemm_kernel(const ConvGroupArgs args) {
 #if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
   using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N, NS>;
   constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
@@ -150,24 +156,43 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
   lds_char* const dma_a = (lds_char*)smem + (wave * 8) * ROW_B;
   lds_char* const dma_b = dma_a + BM * ROW_B;
 
-  auto issue = [&](int stage) {
+  // Buffer offsets of the next K step to fetch.  Within a tap they advance by one step (128 bytes)
+  // per fetch; only when a lane's unit crosses into the next tap are they rebuilt from (rs, c8).
+  // An out-of-range entry stays out of range under the increments (it starts at 2^31).
+  unsigned dma_off[L];
+  auto locate = [&]() {
     const bool u_ok = rs < RS;
     const int r = (rs * p.inv_s) >> 16, s = rs - r * S;
     const int tx = ((r * Wd + s) * C + c8 * 8) * 2, tw = (r * p.wr + s * p.ws + c8 * 8) * 2;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const bool ok = u_ok && ((a_mask[i] >> (rs & 63)) & 1ull);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dma_a + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * i * ROW_B, 16,
-                                               ok ? (unsigned)(a_base[i] + tx) : OOB, 0, 0, 0);
+      dma_off[i] = ok ? (unsigned)(a_base[i] + tx) : OOB;
     }
 #pragma unroll
     for (int j = 0; j < B_IT; ++j) {
       const bool ok = u_ok && ((b_ok >> j) & 1u);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, dma_b + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * j * ROW_B, 16,
-                                               ok ? (unsigned)(b_base[j] + tw) : OOB, 0, 0, 0);
+      dma_off[A_IT + j] = ok ? (unsigned)(b_base[j] + tw) : OOB;
     }
+  };
+  locate();
+  auto issue = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dma_a + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * i * ROW_B, 16,
+                                               dma_off[i], 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < B_IT; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, dma_b + stage * Cfg::STAGE_B + Cfg::PASS_ROWS * j * ROW_B, 16,
+                                               dma_off[A_IT + j], 0, 0, 0);
     c8 += 8;                              // advance one K step
-    while (c8 >= p.C8) { c8 -= p.C8; ++rs; }
+    if (c8 >= p.C8) {
+      do { c8 -= p.C8; ++rs; } while (c8 >= p.C8);
+      locate();
+    } else {
+#pragma unroll
+      for (int i = 0; i < L; ++i) dma_off[i] += BK * 2;
+    }
   };
 
   f32x16 acc[TM][TN];
@@ -254,63 +279,98 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void igemm_kernel(const Con
   float* epi = (float*)smem + wave * 32 * Cfg::EPI_STRIDE;
   constexpr int OCT = WTN / 8;                 // channel octets per staged row
   constexpr int PAIRS = 32 * OCT / 64;         // (row, octet) pairs per lane
+  // ACT, RES (0 none, 1 added before the activation, 2 after) and F32 are uniform over the launch's
+  // problem: one dispatch below instead of per-element tests.
+  auto epilogue = [&](auto act_c, auto res_c, auto f32_c) {
+    constexpr int ACT = decltype(act_c)::value, RES = decltype(res_c)::value;
+    constexpr bool F32 = decltype(f32_c)::value;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] = fmaf(acc[i][j][v], sc[j], sh[j]);
-    // wave-private region: the wave's own LDS writes are visible to its later reads
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
-    __builtin_amdgcn_wave_barrier();
+        for (int v = 0; v < 16; ++v)
+          epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] = fmaf(acc[i][j][v], sc[j], sh[j]);
+      // residual rows of this strip, requested before the staged values are read back
+      uint4 r4[PAIRS];
+      if (RES != 0) {
 #pragma unroll
-    for (int t = 0; t < PAIRS; ++t) {
-      const int id = t * 64 + lane;
-      const int row = id / OCT, oct = id - row * OCT;
-      const int m = m0 + wm * WTM + i * 32 + row;
-      const int k = n0 + wn * WTN + oct * 8;
-      if (m < p.M && k < p.K) {
+        for (int t = 0; t < PAIRS; ++t) {
+          const int id = t * 64 + lane;
+          const int row = id / OCT, oct = id - row * OCT;
+          const int m = m0 + wm * WTM + i * 32 + row;
+          const int k = n0 + wn * WTN + oct * 8;
+          r4[t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
+                                       : make_uint4(0, 0, 0, 0);
+        }
+      }
+      // wave-private region: the wave's own LDS writes are visible to its later reads
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int t = 0; t < PAIRS; ++t) {
+        const int id = t * 64 + lane;
+        const int row = id / OCT, oct = id - row * OCT;
+        const int m = m0 + wm * WTM + i * 32 + row;
+        const int k = n0 + wn * WTN + oct * 8;
         const float4 v0 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8);
         const float4 v1 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8 + 4);
         float val[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
         float rv[8];
-        if (p.res) {
-          const uint4 r4 = *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k);
-          const unsigned ru[4] = {r4.x, r4.y, r4.z, r4.w};
+        if (RES != 0) {
+          const unsigned ru[4] = {r4[t].x, r4[t].y, r4[t].z, r4[t].w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             rv[2 * e] = __uint_as_float(ru[e] << 16);
             rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
           }
-          if (!p.res_after_act) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) val[e] += rv[e];
-          }
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], p.act);
-        if (p.res && p.res_after_act) {
+        if (RES == 1) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) val[e] += rv[e];
         }
-        if (p.out_fp32) {
-          float* yo = (float*)p.y + (long)m * p.y_stride + k;
-          *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
-          *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
-        } else {
-          uint4 o;
-          o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
-          o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
-          o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
-          o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
-          *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], ACT);
+        if (RES == 2) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] += rv[e];
+        }
+        if (m < p.M && k < p.K) {
+          if (F32) {
+            float* yo = (float*)p.y + (long)m * p.y_stride + k;
+            *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
+            *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+          } else {
+            uint4 o;
+            o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
+            o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
+            o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
+            o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
+            *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+          }
         }
       }
+      __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_wave_barrier();
+  };
+  using std::integral_constant;
+  typedef integral_constant<bool, true> yes_t;
+  typedef integral_constant<bool, false> no_t;
+#define SNA_EPI(A, R) epilogue(integral_constant<int, A>{}, integral_constant<int, R>{}, no_t{})
+  const int res_mode = p.res ? (p.res_after_act ? 2 : 1) : 0;
+  if (p.out_fp32) {                                            // logits: no activation, no residual
+    if (p.act == SNA_ACT_NONE && res_mode == 0) epilogue(integral_constant<int, SNA_ACT_NONE>{}, integral_constant<int, 0>{}, yes_t{});
+  } else if (p.act == SNA_ACT_RELU) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_RELU, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_RELU, 1); else SNA_EPI(SNA_ACT_RELU, 2);
+  } else if (p.act == SNA_ACT_NONE) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_NONE, 0); else SNA_EPI(SNA_ACT_NONE, 1);
+  } else if (p.act == SNA_ACT_HSWISH) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_HSWISH, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_HSWISH, 1); else SNA_EPI(SNA_ACT_HSWISH, 2);
+  } else {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_GELU, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_GELU, 1); else SNA_EPI(SNA_ACT_GELU, 2);
   }
+#undef SNA_EPI
 #endif
 }
 
@@ -322,6 +382,10 @@ static const Variant kVariants[] = {
     SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
     SNA_VARIANT(128, 32, 4, 1, 4),  SNA_VARIANT(64, 64, 2, 2, 4),  SNA_VARIANT(64, 128, 1, 4, 3),
     SNA_VARIANT(32, 128, 1, 4, 4),
+#ifdef SNA_EXTRA_VARIANTS
+    SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
+    SNA_VARIANT(128, 96, 4, 1, 4), SNA_VARIANT(128, 32, 4, 1, 2), SNA_VARIANT(128, 64, 4, 1, 4),
+#endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
