@@ -198,6 +198,16 @@ sna_status sna_subnet_forward(sna_supernet* net,
 
 void sna_supernet_free(sna_supernet* net);
 
+/* How long reductions are laid out over blocks.  A conv / linear whose reduction is
+ * longer than 1536 elements is summed in 2 or 4 chunks (a function of the layer's
+ * active shape only), chunk sums added in order in fp32.  mode 0 (default): when a
+ * layer has too few output tiles to fill the GPU, each chunk gets its own blocks
+ * and a second kernel adds the chunk sums; otherwise one block walks all chunks.
+ * mode 1: never spread chunks over blocks.  mode 2: always, when the layer is
+ * chunked.  The logits have the same bits in all three modes; the knob exists
+ * for timing and for checking that property.  Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
+sna_status sna_set_k_split(sna_supernet* net, int32_t mode);
+
 /* Multiply-accumulate count and launch count of the last successful forward on
  * this handle (host bookkeeping for reports). */
 sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t* launches);

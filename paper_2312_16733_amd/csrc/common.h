@@ -19,7 +19,8 @@ enum KClass {
   KC_ATTENTION = 6,
   KC_COPY = 7,       // request gather / logits scatter
   KC_FOLD = 8,       // SubnetNorm statistics folding (load time)
-  KC_COUNT = 9
+  KC_KREDUCE = 9,    // sum of the K-chunk partials + fused epilogue of a split igemm
+  KC_COUNT = 10
 };
 
 // ---- one problem of a grouped launch -------------------------------------------------------
@@ -51,6 +52,13 @@ struct ConvProblem {
   unsigned x_bytes, w_bytes;   // extent of x and of the active weight rows, for bounds-checked loads
   int c_count;          // host bookkeeping: input channels that count as algorithmic work (0 = C)
   int res_after_act;    // 0: y = act(norm(conv) + res); 1: y = act(norm(conv)) + res
+  // K chunking (igemm).  The reduction is cut into chunks of kt_chunk steps of 64 elements, a
+  // function of the layer's active shape only; chunk sums are added in order in fp32.  Either one
+  // block walks all chunks (parts = 1, kt_part >= all steps) or each chunk gets its own blocks
+  // (parts = number of chunks, kt_part = kt_chunk) that write raw fp32 sums for the reduction kernel.
+  int parts, tiles_base;         // tiles = parts * tiles_base
+  int kt_part, kt_chunk;
+  unsigned long part_stride;     // bytes between the parts' fp32 outputs
 };
 
 struct ConvGroupArgs {
@@ -114,8 +122,12 @@ struct PadItem { unsigned long src, dst; unsigned long pixels; };   // byte offs
 #define SNA_PAD_ITEMS 128
 struct PadArgs { const void* src; void* dst; int n; int c_in; PadItem it[SNA_PAD_ITEMS]; };
 
+// fp32 partial sums of split reductions: fixed region at the end of the workspace
+constexpr size_t kPartialBytes = (size_t)64 << 20;
+
 // ---- launchers (defined in the .hip files) ---------------------------------------------------
-hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s);
+hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s);
+hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s);
 void igemm_tile_shape(int variant, int* bm, int* bn);
 int igemm_num_variants();
 hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);

@@ -135,6 +135,7 @@ struct Fwd {
     p.magic_ho = p.Ho > 1 ? (unsigned)((1ull << 32) / (unsigned)p.Ho + 1) : 0;
     if ((double)p.M * (p.Wo > p.Ho ? p.Wo : p.Ho) >= 4294967296.0) err = hipErrorInvalidValue;   // reciprocal range
     p.inv_s = (65536 + p.S - 1) / p.S;
+    p.parts = 1; p.tiles_base = 0; p.kt_part = 1 << 30; p.kt_chunk = 1 << 30; p.part_stride = 0;
     p.y_stride = K; p.res_stride = K;
     const int esize = ti.dtype == SNA_DTYPE_BF16 ? 2 : 4;
     const double xb = (double)p.N * p.H * p.W * p.C * esize, wb = (double)K * p.wk * esize;
@@ -162,46 +163,109 @@ struct Fwd {
     return bn == 128 ? 0 : (bn == 64 ? 1 : 2);
   }
 
+  // K chunking, a function of the reduction length only: the same layer of the same subnet is
+  // summed in the same order whatever it is batched with and however its blocks are laid out.
+  static int chunk_steps(int kt_all) {
+    const int n = kt_all <= 24 ? 1 : (kt_all <= 64 ? 2 : 4);
+    return (kt_all + n - 1) / n;
+  }
+
   void run_igemm(std::vector<ConvProblem>& ps) {
     if (ps.empty()) return;
-    std::vector<int> var(ps.size());
-    for (size_t i = 0; i < ps.size(); ++i) {
-      const ConvProblem& q = ps[i];
+    const size_t n = ps.size();
+    std::vector<int> var(n), chunks(n);
+    long tiles_all = 0;
+    size_t partial_need = 0;
+    bool any_chunked = false;
+    for (size_t i = 0; i < n; ++i) {
+      ConvProblem& q = ps[i];
       if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 64 ||
           (q.out_fp32 && (q.act != SNA_ACT_NONE || q.res))) {
         err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
         return;
       }
       var[i] = pick_variant(q.M, q.K, q.C * q.R * q.S);
+      int bm, bn;
+      igemm_tile_shape(var[i], &bm, &bn);
+      q.tiles_n = (q.K + bn - 1) / bn;
+      q.tiles_base = ((q.M + bm - 1) / bm) * q.tiles_n;
+      tiles_all += q.tiles_base;
+      const int kt_all = (q.K8 + 7) / 8;
+      q.kt_chunk = chunk_steps(kt_all);
+      chunks[i] = (kt_all + q.kt_chunk - 1) / q.kt_chunk;
+      if (chunks[i] > 1) {
+        any_chunked = true;
+        partial_need += align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
+      }
     }
-    for (int v = 0; v < igemm_num_variants(); ++v) {
+    // Too few tiles for the chip: give every chunk its own blocks and sum them in a second launch.
+    const bool split = any_chunked && partial_need <= kPartialBytes &&
+                       (net->split_mode == 2 || (net->split_mode == 0 && tiles_all < 256));
+    std::vector<ConvProblem> reduce;
+    char* part_cur = net->partials;
+    for (size_t i = 0; i < n; ++i) {
+      ConvProblem& q = ps[i];
+      q.parts = 1;
+      q.kt_part = 1 << 30;
+      if (split && chunks[i] > 1) {
+        ConvProblem r = q;               // the reduction finishes the layer: keeps y, norm, residual, activation
+        r.x = part_cur;
+        r.parts = chunks[i];
+        r.part_stride = (unsigned long)q.M * q.K * 4;
+        reduce.push_back(r);
+        q.parts = chunks[i];
+        q.kt_part = q.kt_chunk;
+        q.part_stride = r.part_stride;
+        q.y = part_cur; q.y_stride = q.K; q.out_fp32 = 1;
+        q.scale = nullptr; q.shift = nullptr; q.res = nullptr; q.act = SNA_ACT_NONE;
+        part_cur += align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
+      }
+    }
+    for (int chunked = 0; chunked < 2; ++chunked)
+      for (int v = 0; v < igemm_num_variants(); ++v) {
+        ConvGroupArgs a;
+        a.n = 0;
+        int start = 0;
+        double flops = 0, bytes = 0;
+        for (size_t i = 0; i < n; ++i) {
+          ConvProblem& p = ps[i];
+          // one block walking several chunks folds them in registers: its own kernel instantiation
+          const bool in_block_chunks = p.parts == 1 && chunks[i] > 1;
+          if (var[i] != v || in_block_chunks != (chunked == 1)) continue;
+          if (a.n == SNA_MAX_GROUPS) {       // more problems than one launch carries: flush
+            a.total_tiles = start;
+            launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, chunked == 1, stream); });
+            a.n = 0; start = 0; flops = 0; bytes = 0;
+          }
+          p.tiles = p.tiles_base * p.parts;
+          p.tile_start = start;
+          start += p.tiles;
+          a.p[a.n++] = p;
+          const int cc = p.c_count ? p.c_count : p.C;     // channel padding is not algorithmic work
+          const double mac = (double)p.M * p.K * cc * p.R * p.S;
+          macs += (int64_t)mac;
+          flops += 2 * mac;
+          // algorithmic bytes of the layer (the split path's partial sums are overhead, not counted)
+          bytes += 2.0 * ((double)p.N * p.H * p.W * cc + (double)p.K * p.R * p.S * cc) +
+                   ((p.out_fp32 && p.parts == 1) ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K +
+                   (p.res ? 2.0 * p.M * p.K : 0.0);
+        }
+        a.total_tiles = start;
+        if (a.n) launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, chunked == 1, stream); });
+      }
+    for (size_t i = 0; i < reduce.size(); i += SNA_MAX_GROUPS) {
       ConvGroupArgs a;
       a.n = 0;
-      int bm, bn, start = 0;
-      igemm_tile_shape(v, &bm, &bn);
-      double flops = 0, bytes = 0;
-      for (size_t i = 0; i < ps.size(); ++i) {
-        if (var[i] != v) continue;
-        if (a.n == SNA_MAX_GROUPS) {       // more problems than one launch carries: flush
-          a.total_tiles = start;
-          launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, stream); });
-          a.n = 0; start = 0; flops = 0; bytes = 0;
-        }
-        ConvProblem& p = ps[i];
-        p.tiles_n = (p.K + bn - 1) / bn;
-        p.tiles = ((p.M + bm - 1) / bm) * p.tiles_n;
-        p.tile_start = start;
-        start += p.tiles;
-        a.p[a.n++] = p;
-        const int cc = p.c_count ? p.c_count : p.C;     // channel padding is not algorithmic work
-        const double mac = (double)p.M * p.K * cc * p.R * p.S;
-        macs += (int64_t)mac;
-        flops += 2 * mac;
-        bytes += 2.0 * ((double)p.N * p.H * p.W * cc + (double)p.K * p.R * p.S * cc) +
-                 (p.out_fp32 ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K + (p.res ? 2.0 * p.M * p.K : 0.0);
+      int start = 0;
+      for (size_t j = i; j < reduce.size() && j < i + SNA_MAX_GROUPS; ++j) {
+        ConvProblem& r = reduce[j];
+        r.tiles = (int)(((long)r.M * (r.K / 8) + 255) / 256);
+        r.tile_start = start;
+        start += r.tiles;
+        a.p[a.n++] = r;
       }
       a.total_tiles = start;
-      if (a.n) launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, stream); });
+      launch(KC_KREDUCE, 0, 0, [&] { return launch_splitk_reduce(a, stream); });
     }
   }
 
@@ -809,7 +873,7 @@ int64_t sna_workspace_bytes(const sna_arch_desc* arch, int32_t n_subnets, int32_
   if (st != SNA_OK) return (int64_t)st;
   if (n_subnets < 1 || max_batch < 1) return (int64_t)fail(SNA_E_BATCH, "n_subnets / max_batch < 1");
   return (int64_t)(folded_bytes(t, n_subnets) + (size_t)max_batch * per_request_arena(t) +
-                   (size_t)SNA_MAX_GROUPS * 256 * (NBUF + 2));
+                   (size_t)SNA_MAX_GROUPS * 256 * (NBUF + 2) + kPartialBytes);
 }
 
 sna_status sna_supernet_load(const sna_arch_desc* arch, const void* weights_dev, size_t weights_bytes,
@@ -845,7 +909,8 @@ sna_status sna_supernet_load(const sna_arch_desc* arch, const void* weights_dev,
   net->workspace_bytes = workspace_bytes;
   net->folded = (float*)workspace_dev;
   net->arena = net->workspace + folded_bytes(net->T, n_subnets);
-  net->arena_bytes = workspace_bytes - folded_bytes(net->T, n_subnets);
+  net->arena_bytes = workspace_bytes - folded_bytes(net->T, n_subnets) - kPartialBytes;
+  net->partials = net->arena + net->arena_bytes / 256 * 256;
   net->n_subnets = n_subnets;
   net->max_batch = max_batch;
   hipError_t e = launch_fold_stats(net->stats, net->folded, n_subnets, net->T.row_len, (hipStream_t)hip_stream);
@@ -941,8 +1006,15 @@ sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t
 
 static const char* kClassNames[SNA_N_KCLASS] = {"igemm_conv_linear", "direct_conv", "depthwise", "pool",
                                                 "squeeze_excite", "layernorm", "attention", "copy",
-                                                "fold_stats", "", "", ""};
+                                                "fold_stats", "k_chunk_reduce", "", ""};
 const char* sna_profile_class_name(int32_t k) { return (k >= 0 && k < SNA_N_KCLASS) ? kClassNames[k] : ""; }
+
+sna_status sna_set_k_split(sna_supernet* net, int32_t mode) {
+  if (!net) return fail(SNA_E_NULL, "net is NULL");
+  if (mode < 0 || mode > 2) return fail(SNA_E_CFG_RANGE, "k split mode %d", mode);
+  net->split_mode = mode;
+  return SNA_OK;
+}
 
 sna_status sna_profile_enable(sna_supernet* net, int32_t on) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");

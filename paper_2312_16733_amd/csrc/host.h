@@ -55,6 +55,8 @@ struct sna_supernet {
   float* folded = nullptr;           // [n_subnets][2][row_len]
   char* arena = nullptr;
   size_t arena_bytes = 0;
+  char* partials = nullptr;          // kPartialBytes of fp32 K-chunk sums
+  int split_mode = 0;                // 0 auto, 1 never split a reduction over blocks, 2 always when chunked
   int n_subnets = 0, max_batch = 0;
   // bookkeeping of the last forward
   int64_t last_macs = 0;

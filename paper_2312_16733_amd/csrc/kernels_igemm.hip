@@ -69,8 +69,14 @@ __device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
 // launched with a small LDS request and then run that many blocks per CU.
 constexpr int igemm_min_waves(int bm, int bn) { return bm * bn >= 128 * 128 ? 3 : (bm * bn >= 128 * 96 ? 4 : 5); }
 
-template <int BM, int BN, int WARPS_M, int WARPS_N, int NS>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) void igemm_kernel(const ConvGroupArgs args) {
+// WS (wave-specialised): the block has twice the waves; the second half only fetches (address
+// arithmetic, global->LDS loads, the wait for them), the first half only computes, and the two
+// meet at the one barrier per K step.  A fetching wave stalled on the texture path no longer
+// holds up MFMA issue, which matters when a CU has a single block to overlap with itself.
+template <int BM, int BN, int WARPS_M, int WARPS_N, int NS, bool CHUNKED, bool WS>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * (WS ? 2 : 1),
+                             WS ? (BM * BN >= 128 * 128 ? 2 : 4) : (CHUNKED ? (BM * BN == 128 * 64 ? 3 : 2) : igemm_min_waves(BM, BN)))
+void igemm_kernel(const ConvGroupArgs args) {
 #if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
   using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N, NS>;
   constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
@@ -90,12 +96,21 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
 
   const int g = find_problem(args, tile_id);
   const ConvProblem p = args.p[g];         // by value: uniform fields live in SGPRs across the asm blocks
-  const int local = tile_id - p.tile_start;
+  int local = tile_id - p.tile_start;
+  int part = 0;                            // which K range of the problem this block reduces over
+  if (p.parts > 1) {
+    part = local / p.tiles_base;
+    local -= part * p.tiles_base;
+  }
   const int tn = local % p.tiles_n, tm = local / p.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  constexpr int NW = WARPS_M * WARPS_N;
+  const int lane = threadIdx.x & 63;
+  const bool fetcher = WS && (int)(threadIdx.x >> 6) >= NW;
+  const bool do_load = !WS || fetcher, do_math = !WS || !fetcher;
+  const int wave = WS ? (int)(threadIdx.x >> 6) % NW : (int)(threadIdx.x >> 6);   // index within its role
+  const int tid = wave * 64 + lane;
   const int wm = wave / WARPS_N, wn = wave % WARPS_N;
   const int lrow = tid >> 3;                               // row inside a pass
   const int kc = (tid & 7) ^ ((lrow >> 1) & 7);            // global 16-byte unit this lane's LDS slot holds
@@ -145,9 +160,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
   }
 
   // reduction position of this thread's unit: tap rs and channel octet c8
-  int rs = kc / p.C8;
-  int c8 = kc - rs * p.C8;
-  const int KT = (p.K8 + 7) >> 3;         // K steps of 64 elements
+  const int kt0 = part * p.kt_part;        // first K step of this block's range
+  int rs = (kt0 * 8 + kc) / p.C8;
+  int c8 = kt0 * 8 + kc - rs * p.C8;
+  const int KT_all = (p.K8 + 7) >> 3;     // K steps of 64 elements in the whole reduction
+  const int KT = KT_all - kt0 < p.kt_part ? KT_all - kt0 : p.kt_part;
 
   const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, (int)p.x_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, (int)p.w_bytes, 0x00020000);
@@ -195,13 +212,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
     }
   };
 
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  f32x16 acc[TM][TN];                      // written by the first MFMA of the first step
 
   const int frag_row = lane & 31, frag_hi = lane >> 5, frag_sw = (frag_row >> 1) & 7;
   unsigned frag_off[BK / 16];              // swizzled byte offset of this lane's chunk in each 16-wide slice
@@ -210,7 +221,8 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
   const unsigned a_lane = lds0 + (wm * WTM + frag_row) * ROW_B;
   const unsigned b_lane = lds0 + (BM + wn * WTN + frag_row) * ROW_B;
 
-  auto compute = [&](int stage) {
+  // `fresh`: the accumulators start a new sum at this step (first MFMA of each takes C = 0)
+  auto compute = [&](int stage, const bool fresh) {
     const unsigned ab = a_lane + stage * Cfg::STAGE_B, bb = b_lane + stage * Cfg::STAGE_B;
     u32x4 af[2][TM], bfr[2][TN];
 #pragma unroll
@@ -234,19 +246,31 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
         for (int j = 0; j < TN; ++j) bfr[nxt][j] = lds_read_b128(bb + frag_off[ks + 1], j * 32 * ROW_B);
       }
       __builtin_amdgcn_sched_barrier(0);    // keep the requests ahead of the MFMAs that hide their latency
+      if (ks == 0 && fresh) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[cur][i]),
-                                                              __builtin_bit_cast(bf16x8, bfr[cur][j]), acc[i][j], 0, 0, 0);
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[cur][i]),
+                                                                __builtin_bit_cast(bf16x8, bfr[cur][j]), zero, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[cur][i]),
+                                                                __builtin_bit_cast(bf16x8, bfr[cur][j]), acc[i][j], 0, 0, 0);
+      }
     }
   };
 
   // ---- main loop: ring of NS stages ----------------------------------------------------------
+  if (do_load) {
 #pragma unroll
-  for (int st = 0; st < NS - 1; ++st)
-    if (st < KT) issue(st);
+    for (int st = 0; st < NS - 1; ++st)
+      if (st < KT) issue(st);
+  }
 
   // SubnetNorm scale / shift of this lane's output columns, requested behind the first stages' loads so
   // that they arrive under the main loop
@@ -255,22 +279,50 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int k = n0 + wn * WTN + j * 32 + col_l;
-    sc[j] = (p.scale && k < p.K) ? p.scale[k] : 1.f;
-    sh[j] = (p.shift && k < p.K) ? p.shift[k] : 0.f;
+    sc[j] = (do_math && p.scale && k < p.K) ? p.scale[k] : 1.f;
+    sh[j] = (do_math && p.shift && k < p.K) ? p.shift[k] : 0.f;
   }
 
+  // CHUNKED: the reduction is summed in chunks of p.kt_chunk steps, each accumulated from zero and
+  // added to a running total in fp32, so that one block reducing over all chunks gives the same
+  // bits as one block per chunk plus the reduction kernel.
+  f32x16 tot[CHUNKED ? TM : 1][CHUNKED ? TN : 1];
+  int to_fold = p.kt_chunk;
+  if (CHUNKED) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[i][j][v] = 0.f;
+  }
   int stage = 0, fill = NS - 1;            // stage holding step kt; stage that step kt + NS - 1 goes to
+  bool fresh = true;
   for (int kt = 0; kt < KT; ++kt) {
     // step kt's loads were issued NS-1 steps ago; up to NS-2 newer steps may stay in flight
-    if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    if (do_load) {
+      if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
     __builtin_amdgcn_s_barrier();          // every wave's part of step kt is in LDS; step kt-1 fully consumed
-    if (kt + NS - 1 < KT) issue(fill);
-    compute(stage);
+    if (do_load && kt + NS - 1 < KT) issue(fill);
+    if (do_math) compute(stage, fresh);
+    fresh = false;
     stage = stage + 1 == NS ? 0 : stage + 1;
     fill = fill + 1 == NS ? 0 : fill + 1;
+    if (CHUNKED && --to_fold == 0 && kt + 1 < KT) {       // chunk boundary: bank the chunk's sum
+      to_fold = p.kt_chunk;
+      fresh = true;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tot[i][j][v] = tot[i][j][v] + acc[i][j][v];
+    }
   }
   __syncthreads();
+  if (WS && fetcher) return;               // no barrier below this point
 
   // ---- epilogue -----------------------------------------------------------------------------
   // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of a 32x32 tile.
@@ -290,7 +342,8 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] = fmaf(acc[i][j][v], sc[j], sh[j]);
+          epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] =
+              fmaf(CHUNKED ? tot[i][j][v] + acc[i][j][v] : acc[i][j][v], sc[j], sh[j]);
       // residual rows of this strip, requested before the staged values are read back
       uint4 r4[PAIRS];
       if (RES != 0) {
@@ -338,7 +391,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
         }
         if (m < p.M && k < p.K) {
           if (F32) {
-            float* yo = (float*)p.y + (long)m * p.y_stride + k;
+            float* yo = (float*)((char*)p.y + (size_t)part * p.part_stride) + (long)m * p.y_stride + k;
             *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
             *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
           } else {
@@ -374,17 +427,114 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N, igemm_min_waves(BM, BN)) vo
 #endif
 }
 
-struct Variant { int bm, bn, threads, smem, ns, stage_bytes, epi_bytes; void (*fn)(const ConvGroupArgs); };
+// Second half of a reduction that was split over blocks: adds the fp32 chunk sums in chunk order,
+// then SubnetNorm scale/shift, residual and activation exactly as the fused epilogue does, so
+// the output has the same bits as the one-block-per-tile path.  One thread = 8 channels of a row.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvGroupArgs args) {
+  const int g = find_problem(args, blockIdx.x);
+  const ConvProblem& p = args.p[g];
+  const int k8n = p.K >> 3;
+  const long idx = (long)(blockIdx.x - p.tile_start) * 256 + threadIdx.x;
+  if (idx >= (long)p.M * k8n) return;
+  const int m = (int)(idx / k8n);
+  const int k = (int)(idx - (long)m * k8n) * 8;
+  // all loads first (at most 4 chunks), then the sums in chunk order
+  const float* src = (const float*)p.x + (long)m * p.K + k;
+  float4 pa[4], pb[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (c < p.parts) {
+      const float* sp = (const float*)((const char*)src + (size_t)c * p.part_stride);
+      pa[c] = *(const float4*)sp;
+      pb[c] = *(const float4*)(sp + 4);
+    }
+  }
+  float4 sc0 = make_float4(1.f, 1.f, 1.f, 1.f), sc1 = sc0, sh0 = make_float4(0.f, 0.f, 0.f, 0.f), sh1 = sh0;
+  // the per-channel vectors are only guaranteed 4-byte alignment
+  auto load8 = [&](const float* v, float4& lo, float4& hi) {
+    if (((size_t)v & 15) == 0) {
+      lo = *(const float4*)(v + k);
+      hi = *(const float4*)(v + k + 4);
+    } else {
+      lo = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+      hi = make_float4(v[k + 4], v[k + 5], v[k + 6], v[k + 7]);
+    }
+  };
+  if (p.scale) load8(p.scale, sc0, sc1);
+  if (p.shift) load8(p.shift, sh0, sh1);
+  uint4 r4 = make_uint4(0, 0, 0, 0);
+  if (p.res) r4 = *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k);
+  float val[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (c < p.parts) {
+      val[0] = val[0] + pa[c].x; val[1] = val[1] + pa[c].y; val[2] = val[2] + pa[c].z; val[3] = val[3] + pa[c].w;
+      val[4] = val[4] + pb[c].x; val[5] = val[5] + pb[c].y; val[6] = val[6] + pb[c].z; val[7] = val[7] + pb[c].w;
+    }
+  }
+  const float scv[8] = {sc0.x, sc0.y, sc0.z, sc0.w, sc1.x, sc1.y, sc1.z, sc1.w};
+  const float shv[8] = {sh0.x, sh0.y, sh0.z, sh0.w, sh1.x, sh1.y, sh1.z, sh1.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = fmaf(val[e], scv[e], shv[e]);
+  float rv[8];
+  if (p.res) {
+    const unsigned ru[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      rv[2 * e] = __uint_as_float(ru[e] << 16);
+      rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
+    }
+    if (!p.res_after_act) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[e] += rv[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], p.act);
+  if (p.res && p.res_after_act) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) val[e] += rv[e];
+  }
+  if (p.out_fp32) {
+    float* yo = (float*)p.y + (long)m * p.y_stride + k;
+    *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
+    *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+  } else {
+    uint4 o;
+    o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
+    o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
+    o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
+    o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
+    *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+  }
+}
+
+hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s) {
+  if (a.n == 0 || a.total_tiles == 0) return hipSuccess;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(a.total_tiles), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+struct Variant { int bm, bn, threads, smem, ns, stage_bytes, epi_bytes; void (*fn)(const ConvGroupArgs); void (*fn_chunked)(const ConvGroupArgs); };
 #define SNA_VARIANT(BM, BN, WM, WN, NS) \
   { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
-    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS> }
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, false>, igemm_kernel<BM, BN, WM, WN, NS, true, false> }
 static const Variant kVariants[] = {
     SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
     SNA_VARIANT(128, 32, 4, 1, 4),  SNA_VARIANT(64, 64, 2, 2, 4),  SNA_VARIANT(64, 128, 1, 4, 3),
     SNA_VARIANT(32, 128, 1, 4, 4),
 #ifdef SNA_EXTRA_VARIANTS
+#define SNA_WS_VARIANT(BM, BN, WM, WN, NS) \
+  { BM, BN, 128 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, true>, igemm_kernel<BM, BN, WM, WN, NS, true, true> }
     SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
     SNA_VARIANT(128, 96, 4, 1, 4), SNA_VARIANT(128, 32, 4, 1, 2), SNA_VARIANT(128, 64, 4, 1, 4),
+    SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 3), SNA_WS_VARIANT(128, 128, 2, 2, 4),   // 14 15 16
+    SNA_WS_VARIANT(128, 64, 2, 2, 3), SNA_WS_VARIANT(128, 96, 4, 1, 3), SNA_WS_VARIANT(64, 128, 1, 4, 3),     // 17 18 19
+    SNA_WS_VARIANT(64, 128, 1, 4, 4), SNA_WS_VARIANT(64, 64, 2, 2, 4), SNA_WS_VARIANT(32, 128, 1, 4, 4),      // 20 21 22
+    SNA_WS_VARIANT(128, 64, 2, 2, 2), SNA_WS_VARIANT(64, 128, 1, 4, 2),                                       // 23 24
 #endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -395,27 +545,29 @@ void igemm_tile_shape(int variant, int* bm, int* bn) {
   *bn = kVariants[variant].bn;
 }
 
-hipError_t launch_igemm(const ConvGroupArgs& a, int variant, hipStream_t s) {
+hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s) {
   if (a.n == 0) return hipSuccess;
   if (variant < 0 || variant >= kNumVariants) return hipErrorInvalidValue;
-  static bool attr_done[kNumVariants] = {false};
+  static bool attr_done[kNumVariants][2] = {};
   const Variant& v = kVariants[variant];
-  if (!attr_done[variant]) {
-    hipError_t e = hipFuncSetAttribute((const void*)v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.smem);
+  void (*fn)(const ConvGroupArgs) = chunked ? v.fn_chunked : v.fn;
+  if (!attr_done[variant][chunked]) {
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.smem);
     if (e != hipSuccess) return e;
-    attr_done[variant] = true;
+    attr_done[variant][chunked] = true;
   }
   // a launch whose problems all have fewer K steps than the ring has stages only touches the
   // leading stages: asking for less LDS lets more blocks share a CU
   int kt_max = 1;
   for (int i = 0; i < a.n; ++i) {
-    const int kt = (a.p[i].K8 + 7) >> 3;
+    int kt = (a.p[i].K8 + 7) >> 3;
+    if (kt > a.p[i].kt_part) kt = a.p[i].kt_part;
     if (kt > kt_max) kt_max = kt;
   }
   const int stages = kt_max < v.ns ? kt_max : v.ns;
   const int smem = stages * v.stage_bytes > v.epi_bytes ? stages * v.stage_bytes : v.epi_bytes;
   const int blocks = (a.total_tiles + 7) / 8 * 8;
-  hipLaunchKernelGGL(v.fn, dim3(blocks), dim3(v.threads), smem, s, a);
+  hipLaunchKernelGGL(fn, dim3(blocks), dim3(v.threads), smem, s, a);
   return hipGetLastError();
 }
 

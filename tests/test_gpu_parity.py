@@ -411,3 +411,37 @@ def test_max_batch_boundary_and_workspace_check(torch_mod):
                           net.stats.numel() * 4, 8, 4, small.data_ptr(), small.numel(), 0)
     assert ei.value.status == -7
     net.close()
+
+
+def test_k_split_modes_give_identical_bits(torch_mod, resnet_full, tf_full):
+    """Long reductions are summed in shape-determined chunks; whether one block walks the chunks
+    or each chunk has its own blocks plus the reduction kernel must not change a bit."""
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    try:
+        for ci, batch in ((15, 3), (8, 16), (0, 64)):
+            c = C[ci]
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 14)
+            outs = []
+            for mode in (1, 2, 0):
+                net.set_k_split(mode)
+                say("k split mode", mode, "resnet cfg", ci, "batch", batch)
+                outs.append(run_single(torch, net, spec, c, x))
+            np.testing.assert_array_equal(outs[0], outs[1])
+            np.testing.assert_array_equal(outs[0], outs[2])
+    finally:
+        net.set_k_split(0)
+    spec, W, S, C, net = tf_full
+    try:
+        c = C[11]
+        x = synth.make_inputs(spec, 4, c.in_h, c.in_w, 15)
+        outs = []
+        for mode in (1, 2, 0):
+            net.set_k_split(mode)
+            say("k split mode", mode, "transformer cfg 11 batch 4")
+            outs.append(run_tf(torch, net, spec, [c], np.zeros(4, np.int32), x))
+        for o in outs[1:]:
+            np.testing.assert_array_equal(outs[0][0], o[0])
+            np.testing.assert_array_equal(outs[0][1], o[1])
+    finally:
+        net.set_k_split(0)
