@@ -196,6 +196,23 @@ sna_status sna_subnet_forward(sna_supernet* net,
                               const void* inputs_dev, float* logits_dev,
                               void* hidden_dev, void* hip_stream);
 
+/* Same arguments and result as sna_subnet_forward, but every conv / linear layer
+ * shape met for the first time on this handle is timed with each tile variant of
+ * the matrix kernel (a few launches each, synchronising on the stream), and the
+ * fastest is remembered for later sna_subnet_forward calls with that layer shape.
+ * The paper's serving system profiles each subnet offline before serving; this
+ * is the same step for the kernels.  Tile variants do not change a bit of the
+ * result.  Returns after the stream has drained.  Not for use under stream
+ * capture.  Errors: as sna_subnet_forward. */
+sna_status sna_subnet_tune(sna_supernet* net,
+                           const sna_subnet_cfg* cfgs, int32_t n_cfgs,
+                           const int32_t* req_cfg, int32_t n_requests,
+                           const void* inputs_dev, float* logits_dev,
+                           void* hidden_dev, void* hip_stream);
+
+/* Number of layer shapes with a measured tile variant on this handle. */
+int32_t sna_tuned_count(const sna_supernet* net);
+
 void sna_supernet_free(sna_supernet* net);
 
 /* How long reductions are laid out over blocks.  A conv / linear whose reduction is

@@ -82,6 +82,8 @@ def lib():
     L.sna_supernet_load.restype = i32
     L.sna_subnet_forward.argtypes = [vp, C.POINTER(SubnetCfgC), i32, C.POINTER(i32), i32, vp, vp, vp, vp]
     L.sna_subnet_forward.restype = i32
+    L.sna_subnet_tune.argtypes = L.sna_subnet_forward.argtypes; L.sna_subnet_tune.restype = i32
+    L.sna_tuned_count.argtypes = [vp]; L.sna_tuned_count.restype = i32
     L.sna_supernet_free.argtypes = [vp]; L.sna_supernet_free.restype = None
     L.sna_last_forward_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32)]; L.sna_last_forward_info.restype = i32
     L.sna_profile_enable.argtypes = [vp, i32]; L.sna_profile_enable.restype = i32
@@ -215,12 +217,14 @@ def supernet_load(arch, weights_dev_ptr, weights_bytes, stats_dev_ptr, stats_byt
     return h
 
 
-def subnet_forward(handle, cfgs_c, req_cfg, inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr=None, stream=0):
+def subnet_forward(handle, cfgs_c, req_cfg, inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr=None, stream=0,
+                   tune=False):
     n_cfgs = len(cfgs_c)
     arr = cfgs_c if isinstance(cfgs_c, C.Array) else (SubnetCfgC * n_cfgs)(*cfgs_c)
     rc = np.ascontiguousarray(req_cfg, dtype=np.int32)
-    _check(lib().sna_subnet_forward(handle, arr, n_cfgs, rc.ctypes.data_as(C.POINTER(C.c_int32)),
-                                    len(rc), inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr, stream))
+    fn = lib().sna_subnet_tune if tune else lib().sna_subnet_forward
+    _check(fn(handle, arr, n_cfgs, rc.ctypes.data_as(C.POINTER(C.c_int32)),
+              len(rc), inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr, stream))
 
 
 class Supernet:
@@ -261,7 +265,14 @@ class Supernet:
     def prepare_cfgs(self, cfgs):
         return (SubnetCfgC * len(cfgs))(*[cfg_to_c(c) for c in cfgs])
 
-    def forward(self, cfgs, req_cfg, inputs, logits=None, hidden=None, stream=None):
+    def tune(self, cfgs, req_cfg, inputs, hidden=None, stream=None):
+        """One forward that also measures the tile variants of every layer shape it meets."""
+        return self.forward(cfgs, req_cfg, inputs, hidden=hidden, stream=stream, tune=True)
+
+    def tuned_count(self):
+        return int(lib().sna_tuned_count(self.handle))
+
+    def forward(self, cfgs, req_cfg, inputs, logits=None, hidden=None, stream=None, tune=False):
         """inputs: device tensor of the architecture's dtype, requests concatenated (flat is fine)."""
         torch = self.torch
         cfgs_c = cfgs if isinstance(cfgs, C.Array) else self.prepare_cfgs(cfgs)
@@ -272,7 +283,7 @@ class Supernet:
         if stream is None:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         subnet_forward(self.handle, cfgs_c, req_cfg, inputs.data_ptr(), logits.data_ptr(),
-                       hidden.data_ptr() if hidden is not None else None, stream)
+                       hidden.data_ptr() if hidden is not None else None, stream, tune=tune)
         return logits
 
     def last_forward_info(self):

@@ -163,6 +163,67 @@ struct Fwd {
     return bn == 128 ? 0 : (bn == 64 ? 1 : 2);
   }
 
+  // Fill the launch-side fields of a problem for tile variant v (parts already decided).
+  static void place(ConvProblem& q, int v) {
+    int bm, bn;
+    igemm_tile_shape(v, &bm, &bn);
+    q.tiles_n = (q.K + bn - 1) / bn;
+    q.tiles_base = ((q.M + bm - 1) / bm) * q.tiles_n;
+    q.tiles = q.tiles_base * q.parts;
+  }
+
+  // Time every tile variant on this one problem (followed by its reduction launch when the
+  // reduction is split over blocks) and return the fastest; *best_ms gets its time per run.
+  // Runs the problem for real (outputs are rewritten with the same values each time) and
+  // synchronises on the stream.
+  int measure_variants(const ConvProblem& q, bool chunked, const ConvProblem* reduce, float* best_ms) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { err = hipErrorUnknown; return 0; }
+    ConvGroupArgs ra;
+    if (reduce) {
+      ra.n = 1;
+      ra.p[0] = *reduce;
+      ra.p[0].tiles = (int)(((long)reduce->M * (reduce->K / 8) + 255) / 256);
+      ra.p[0].tile_start = 0;
+      ra.total_tiles = ra.p[0].tiles;
+    }
+    int best = -1;
+    *best_ms = 0.f;
+    for (int v = 0; v < igemm_num_variants() && err == hipSuccess; ++v) {
+      ConvGroupArgs a;
+      a.n = 1;
+      a.p[0] = q;
+      place(a.p[0], v);
+      a.p[0].tile_start = 0;
+      a.total_tiles = a.p[0].tiles;
+      auto once = [&] {
+        err = launch_igemm(a, v, chunked, stream);
+        if (err == hipSuccess && reduce) err = launch_splitk_reduce(ra, stream);
+      };
+      once();                                            // loads the code object, warms the caches
+      float v_ms = 0.f;
+      for (int trial = 0; trial < 2 && err == hipSuccess; ++trial) {
+        const int reps = 4;
+        err = hipEventRecord(e0, stream);
+        for (int r = 0; r < reps && err == hipSuccess; ++r) once();
+        if (err == hipSuccess) err = hipEventRecord(e1, stream);
+        if (err == hipSuccess) err = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+        ms /= reps;
+        if (trial == 0 || ms < v_ms) v_ms = ms;
+      }
+      if (err == hipSuccess && (best < 0 || v_ms < *best_ms)) { best = v; *best_ms = v_ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return best < 0 ? 0 : best;
+  }
+
+  static std::array<int, 6> tune_key(const ConvProblem& q, int parts) {
+    return {q.M, q.K, q.C, q.R * q.S, q.stride, parts};
+  }
+
   // K chunking, a function of the reduction length only: the same layer of the same subnet is
   // summed in the same order whatever it is batched with and however its blocks are laid out.
   static int chunk_steps(int kt_all) {
@@ -175,8 +236,6 @@ struct Fwd {
     const size_t n = ps.size();
     std::vector<int> var(n), chunks(n);
     long tiles_all = 0;
-    size_t partial_need = 0;
-    bool any_chunked = false;
     for (size_t i = 0; i < n; ++i) {
       ConvProblem& q = ps[i];
       if (q.C % 8 || q.K % 8 || q.y_stride % 8 || q.res_stride % 8 || q.R * q.S > 64 ||
@@ -184,43 +243,62 @@ struct Fwd {
         err = hipErrorInvalidValue;      // shapes the MFMA path does not take; callers route these elsewhere
         return;
       }
-      var[i] = pick_variant(q.M, q.K, q.C * q.R * q.S);
-      int bm, bn;
-      igemm_tile_shape(var[i], &bm, &bn);
-      q.tiles_n = (q.K + bn - 1) / bn;
-      q.tiles_base = ((q.M + bm - 1) / bm) * q.tiles_n;
+      q.parts = 1;
+      q.kt_part = 1 << 30;
+      auto it = net->tuned.find(tune_key(q, 1));
+      var[i] = it != net->tuned.end() ? it->second : pick_variant(q.M, q.K, q.C * q.R * q.S);
+      place(q, var[i]);
       tiles_all += q.tiles_base;
       const int kt_all = (q.K8 + 7) / 8;
       q.kt_chunk = chunk_steps(kt_all);
       chunks[i] = (kt_all + q.kt_chunk - 1) / q.kt_chunk;
-      if (chunks[i] > 1) {
-        any_chunked = true;
-        partial_need += align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
-      }
     }
-    // Too few tiles for the chip: give every chunk its own blocks and sum them in a second launch.
-    const bool split = any_chunked && partial_need <= kPartialBytes &&
-                       (net->split_mode == 2 || (net->split_mode == 0 && tiles_all < 256));
+    // Too few tiles for the chip: give every chunk its own blocks and sum them in a second launch
+    // (a measured per-shape decision, where there is one, takes precedence).
+    const bool split_rule = net->split_mode == 2 || (net->split_mode == 0 && tiles_all < 256);
     std::vector<ConvProblem> reduce;
     char* part_cur = net->partials;
     for (size_t i = 0; i < n; ++i) {
       ConvProblem& q = ps[i];
-      q.parts = 1;
-      q.kt_part = 1 << 30;
-      if (split && chunks[i] > 1) {
-        ConvProblem r = q;               // the reduction finishes the layer: keeps y, norm, residual, activation
+      const size_t part_bytes = align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
+      const bool can_split = chunks[i] > 1 && (size_t)(part_cur - net->partials) + part_bytes <= kPartialBytes;
+      ConvProblem r = q, qs = q;         // the reduction finishes the layer: keeps y, norm, residual, activation
+      if (can_split) {
         r.x = part_cur;
         r.parts = chunks[i];
         r.part_stride = (unsigned long)q.M * q.K * 4;
-        reduce.push_back(r);
-        q.parts = chunks[i];
-        q.kt_part = q.kt_chunk;
-        q.part_stride = r.part_stride;
-        q.y = part_cur; q.y_stride = q.K; q.out_fp32 = 1;
-        q.scale = nullptr; q.shift = nullptr; q.res = nullptr; q.act = SNA_ACT_NONE;
-        part_cur += align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
+        qs.parts = chunks[i];
+        qs.kt_part = q.kt_chunk;
+        qs.part_stride = r.part_stride;
+        qs.y = part_cur; qs.y_stride = q.K; qs.out_fp32 = 1;
+        qs.scale = nullptr; qs.shift = nullptr; qs.res = nullptr; qs.act = SNA_ACT_NONE;
       }
+      bool split = can_split && split_rule;
+      if (can_split && net->split_mode == 0) {
+        const auto key = tune_key(q, 0);
+        if (net->tuning && !net->tuned_split.count(key)) {
+          float t_one = 0.f, t_split = 0.f;
+          net->tuned[tune_key(q, 1)] = measure_variants(q, true, nullptr, &t_one);
+          net->tuned[tune_key(q, chunks[i])] = measure_variants(qs, false, &r, &t_split);
+          net->tuned_split[key] = t_split < t_one ? 1 : 0;
+        }
+        auto it = net->tuned_split.find(key);
+        if (it != net->tuned_split.end()) split = it->second != 0;
+      }
+      if (split) {
+        q = qs;
+        reduce.push_back(r);
+        part_cur += part_bytes;
+      }
+      if (net->tuning && !net->tuned.count(tune_key(q, q.parts))) {
+        float t = 0.f;
+        net->tuned[tune_key(q, q.parts)] = measure_variants(q, q.parts == 1 && chunks[i] > 1, split ? &r : nullptr, &t);
+      }
+      auto it = net->tuned.find(tune_key(q, q.parts));
+      if (it != net->tuned.end()) var[i] = it->second;
+      place(q, var[i]);
     }
+    if (err != hipSuccess) return;
     for (int chunked = 0; chunked < 2; ++chunked)
       for (int v = 0; v < igemm_num_variants(); ++v) {
         ConvGroupArgs a;
@@ -237,7 +315,6 @@ struct Fwd {
             launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, chunked == 1, stream); });
             a.n = 0; start = 0; flops = 0; bytes = 0;
           }
-          p.tiles = p.tiles_base * p.parts;
           p.tile_start = start;
           start += p.tiles;
           a.p[a.n++] = p;
@@ -1008,6 +1085,19 @@ static const char* kClassNames[SNA_N_KCLASS] = {"igemm_conv_linear", "direct_con
                                                 "squeeze_excite", "layernorm", "attention", "copy",
                                                 "fold_stats", "k_chunk_reduce", "", ""};
 const char* sna_profile_class_name(int32_t k) { return (k >= 0 && k < SNA_N_KCLASS) ? kClassNames[k] : ""; }
+
+sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs, const int32_t* req_cfg,
+                           int32_t n_requests, const void* inputs_dev, float* logits_dev, void* hidden_dev,
+                           void* hip_stream) {
+  if (!net) return fail(SNA_E_NULL, "net is NULL");
+  net->tuning = true;
+  sna_status st = sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
+  net->tuning = false;
+  if (st == SNA_OK && hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return fail(SNA_E_HIP, "stream synchronize");
+  return st;
+}
+
+int32_t sna_tuned_count(const sna_supernet* net) { return net ? (int32_t)(net->tuned.size() + net->tuned_split.size()) : 0; }
 
 sna_status sna_set_k_split(sna_supernet* net, int32_t mode) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");

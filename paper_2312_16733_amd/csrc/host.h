@@ -1,5 +1,6 @@
 // Host-side state of a resident SuperNet and of one forward call.
 #pragma once
+#include <array>
 #include <map>
 #include <string>
 #include <vector>
@@ -57,6 +58,11 @@ struct sna_supernet {
   size_t arena_bytes = 0;
   char* partials = nullptr;          // kPartialBytes of fp32 K-chunk sums
   int split_mode = 0;                // 0 auto, 1 never split a reduction over blocks, 2 always when chunked
+  // tile variant measured best for a layer shape: (M, K_out, C_in, R*S, stride, parts) -> variant
+  std::map<std::array<int, 6>, int> tuned;
+  // measured for a chunked layer shape: 1 = one block per K chunk plus the reduction kernel is faster
+  std::map<std::array<int, 6>, int> tuned_split;
+  bool tuning = false;               // the forward in progress measures shapes it has no entry for
   int n_subnets = 0, max_batch = 0;
   // bookkeeping of the last forward
   int64_t last_macs = 0;

@@ -521,20 +521,21 @@ struct Variant { int bm, bn, threads, smem, ns, stage_bytes, epi_bytes; void (*f
 #define SNA_VARIANT(BM, BN, WM, WN, NS) \
   { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
     IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, false>, igemm_kernel<BM, BN, WM, WN, NS, true, false> }
+#define SNA_WS_VARIANT(BM, BN, WM, WN, NS) \
+  { BM, BN, 128 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, true>, igemm_kernel<BM, BN, WM, WN, NS, true, true> }
+// 0..6 are the variants the shape heuristic chooses from; the rest are reached through tuning only.
 static const Variant kVariants[] = {
     SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
     SNA_VARIANT(128, 32, 4, 1, 4),  SNA_VARIANT(64, 64, 2, 2, 4),  SNA_VARIANT(64, 128, 1, 4, 3),
     SNA_VARIANT(32, 128, 1, 4, 4),
+    SNA_WS_VARIANT(64, 64, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 3), SNA_WS_VARIANT(128, 64, 2, 2, 3),
+    SNA_WS_VARIANT(128, 96, 4, 1, 3), SNA_WS_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 32, 4, 1, 2),
+    SNA_WS_VARIANT(32, 128, 1, 4, 4),
 #ifdef SNA_EXTRA_VARIANTS
-#define SNA_WS_VARIANT(BM, BN, WM, WN, NS) \
-  { BM, BN, 128 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
-    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, true>, igemm_kernel<BM, BN, WM, WN, NS, true, true> }
     SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
-    SNA_VARIANT(128, 96, 4, 1, 4), SNA_VARIANT(128, 32, 4, 1, 2), SNA_VARIANT(128, 64, 4, 1, 4),
-    SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 3), SNA_WS_VARIANT(128, 128, 2, 2, 4),   // 14 15 16
-    SNA_WS_VARIANT(128, 64, 2, 2, 3), SNA_WS_VARIANT(128, 96, 4, 1, 3), SNA_WS_VARIANT(64, 128, 1, 4, 3),     // 17 18 19
-    SNA_WS_VARIANT(64, 128, 1, 4, 4), SNA_WS_VARIANT(64, 64, 2, 2, 4), SNA_WS_VARIANT(32, 128, 1, 4, 4),      // 20 21 22
-    SNA_WS_VARIANT(128, 64, 2, 2, 2), SNA_WS_VARIANT(64, 128, 1, 4, 2),                                       // 23 24
+    SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 4),
+    SNA_WS_VARIANT(128, 64, 2, 2, 2), SNA_WS_VARIANT(64, 128, 1, 4, 2),
 #endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);

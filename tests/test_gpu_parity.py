@@ -445,3 +445,30 @@ def test_k_split_modes_give_identical_bits(torch_mod, resnet_full, tf_full):
             np.testing.assert_array_equal(outs[0][1], o[1])
     finally:
         net.set_k_split(0)
+
+
+def test_tuned_tile_variants_do_not_change_bits(torch_mod):
+    """sna_subnet_tune measures tile variants (and whether to spread K chunks over blocks) per layer
+    shape; the choice must not change the result, and the tuned forward still matches the oracle."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.ResNetSpec()
+    W, S, C = setup(spec, 16)
+    net = sna.Supernet(spec, W, S, 16, 64)
+    try:
+        for ci, batch in ((3, 2), (15, 1), (9, 16)):
+            c = C[ci]
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 16)
+            before = run_single(torch, net, spec, c, x)
+            n0 = net.tuned_count()
+            say("tune resnet cfg", ci, "batch", batch)
+            tuned_out = net.tune([c], np.zeros(batch, np.int32), to_dev(torch, spec, x))
+            torch.cuda.synchronize()
+            assert net.tuned_count() > n0
+            after = run_single(torch, net, spec, c, x)
+            np.testing.assert_array_equal(before, tuned_out.cpu().numpy())
+            np.testing.assert_array_equal(before, after)
+            check_parity(after[:1], oracle.forward(spec, W, S, c, x[:1]), "bf16", f"tuned cfg {ci}")
+    finally:
+        net.close()
