@@ -78,7 +78,7 @@ struct Fwd {
   std::vector<Group> groups;
   hipError_t err = hipSuccess;
   int64_t macs = 0;
-  int launches = 0;
+  std::vector<PlanOp> ops;
 
   const ArchTables& T() const { return net->T; }
   int esz() const { return net->T.esz; }
@@ -100,22 +100,15 @@ struct Fwd {
     }
     return net->ev_pool[net->ev_used++];
   }
-  template <class F>
-  void launch(int kc, double flops, double bytes, F&& f) {
+  // Record one launch.  Nothing runs here: the list is executed (and kept for replay) afterwards.
+  template <class A>
+  void emit(PlanOp::Type type, int variant, int flag, int kc, double flops, double bytes, const A& a) {
     if (err != hipSuccess) return;
-    hipEvent_t a = nullptr, b = nullptr;
-    if (net->prof_on) {
-      a = next_event(); b = next_event();
-      if (a && b && hipEventRecord(a, stream) != hipSuccess) a = b = nullptr;
-    }
-    err = f();
-    if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
-      net->prof_recs.push_back({kc, a, b});
-      net->prof_flops[kc] += flops;
-      net->prof_bytes[kc] += bytes;
-      net->prof_launches[kc] += 1;
-    }
-    ++launches;
+    ops.emplace_back();
+    PlanOp& op = ops.back();
+    op.type = type; op.variant = variant; op.flag = flag; op.kc = kc; op.flops = flops; op.bytes = bytes;
+    op.args.resize(sizeof(A));
+    memcpy(op.args.data(), &a, sizeof(A));
   }
 
   // ---- conv / linear ---------------------------------------------------------------------------
@@ -312,7 +305,7 @@ struct Fwd {
           if (var[i] != v || in_block_chunks != (chunked == 1)) continue;
           if (a.n == SNA_MAX_GROUPS) {       // more problems than one launch carries: flush
             a.total_tiles = start;
-            launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, chunked == 1, stream); });
+            emit(PlanOp::IGEMM, v, chunked, KC_IGEMM, flops, bytes, a);
             a.n = 0; start = 0; flops = 0; bytes = 0;
           }
           p.tile_start = start;
@@ -328,7 +321,7 @@ struct Fwd {
                    (p.res ? 2.0 * p.M * p.K : 0.0);
         }
         a.total_tiles = start;
-        if (a.n) launch(KC_IGEMM, flops, bytes, [&] { return launch_igemm(a, v, chunked == 1, stream); });
+        if (a.n) emit(PlanOp::IGEMM, v, chunked, KC_IGEMM, flops, bytes, a);
       }
     for (size_t i = 0; i < reduce.size(); i += SNA_MAX_GROUPS) {
       ConvGroupArgs a;
@@ -342,7 +335,7 @@ struct Fwd {
         a.p[a.n++] = r;
       }
       a.total_tiles = start;
-      launch(KC_KREDUCE, 0, 0, [&] { return launch_splitk_reduce(a, stream); });
+      emit(PlanOp::KREDUCE, 0, 0, KC_KREDUCE, 0, 0, a);
     }
   }
 
@@ -366,7 +359,7 @@ struct Fwd {
                (p.res ? (double)esz() * p.M * p.K : 0.0);
     }
     a.total_tiles = start;
-    launch(KC_DIRECT, flops, bytes, [&] { return launch_direct_conv(a, T().arch.dtype, stream); });
+    emit(PlanOp::DIRECT, 0, T().arch.dtype, KC_DIRECT, flops, bytes, a);
   }
 
   // One conv slot over all groups.  `fill` returns false for groups that skip the slot.
@@ -404,8 +397,8 @@ struct Fwd {
     }
     if (!a.n) return;
     const int dt = T().arch.dtype;
-    if (is_max) launch(KC_POOL, 0, bytes, [&] { return launch_maxpool(a, dt, stream); });
-    else launch(KC_POOL, 0, bytes, [&] { return launch_gap(a, dt, stream); });
+    if (is_max) emit(PlanOp::MAXPOOL, 0, dt, KC_POOL, 0, bytes, a);
+    else emit(PlanOp::GAP, 0, dt, KC_POOL, 0, bytes, a);
   }
 
   void dw_slot(const std::function<bool(Group&, DwProblem&)>& fill) {
@@ -421,7 +414,7 @@ struct Fwd {
       bytes += 2.0 * p.N * p.C * ((double)p.H * p.W + (double)p.Ho * p.Wo) + 2.0 * p.k * p.k * p.C + 8.0 * p.C;
       a.p[a.n++] = p;
     }
-    if (a.n) launch(KC_DEPTHWISE, flops, bytes, [&] { return launch_depthwise(a, stream); });
+    if (a.n) emit(PlanOp::DW, 0, 0, KC_DEPTHWISE, flops, bytes, a);
   }
   // Depthwise WeightSlice: leading C channels, centre k x k window of the stored kernel.
   void slice_dw(DwProblem& p, const sna_tensor_info& ti, int k, int stride) {
@@ -445,7 +438,7 @@ struct Fwd {
       bytes += 4.0 * p.N * p.HW * p.C + 4.0 * p.C * p.Q;
       a.p[a.n++] = p;
     }
-    if (a.n) launch(KC_SE, flops, bytes, [&] { return launch_se(a, stream); });
+    if (a.n) emit(PlanOp::SE, 0, 0, KC_SE, flops, bytes, a);
   }
 
   // ---- request gather / logits scatter -----------------------------------------------------
@@ -456,7 +449,7 @@ struct Fwd {
       a.n = (int)std::min<size_t>(SNA_COPY_ITEMS, items.size() - i);
       double bytes = 0;
       for (int j = 0; j < a.n; ++j) { a.it[j] = items[i + j]; bytes += 2.0 * items[i + j].n; }
-      launch(KC_COPY, 0, bytes, [&] { return launch_copy(a, stream); });
+      emit(PlanOp::COPY, 0, 0, KC_COPY, 0, bytes, a);
     }
   }
 
@@ -505,7 +498,7 @@ struct Fwd {
       a.n = (int)std::min<size_t>(SNA_PAD_ITEMS, items.size() - i);
       double bytes = 0;
       for (int j = 0; j < a.n; ++j) { a.it[j] = items[i + j]; bytes += (2.0 * c_in + 16.0) * items[i + j].pixels; }
-      launch(KC_COPY, 0, bytes, [&] { return launch_pad_input(a, stream); });
+      emit(PlanOp::PAD, 0, 0, KC_COPY, 0, bytes, a);
     }
   }
 
@@ -811,7 +804,7 @@ sna_status Fwd::run_transformer(const void*, float* logits, void* hidden) {
       la.p[la.n++] = p;
     }
     (void)to_cur_other;
-    if (la.n) launch(KC_LAYERNORM, 0, bytes, [&] { return launch_layernorm(la, stream); });
+    if (la.n) emit(PlanOp::LN, 0, 0, KC_LAYERNORM, 0, bytes, la);
   };
   for (int j = 0; j < a.max_layers; ++j) {
     const std::string pre = "l" + std::to_string(j) + ".";
@@ -841,7 +834,7 @@ sna_status Fwd::run_transformer(const void*, float* logits, void* hidden) {
       abytes += 2.0 * 4 * p.B * S * at;
       aa.p[aa.n++] = p;
     }
-    launch(KC_ATTENTION, aflops, abytes, [&] { return launch_attention(aa, stream); });
+    emit(PlanOp::ATTN, 0, 0, KC_ATTENTION, aflops, abytes, aa);
     ps.clear();
     for (Group& g : groups) {
       if (j >= g.cfg->depth[0]) continue;
@@ -901,6 +894,99 @@ static size_t per_request_arena(const ArchTables& T) {
 }  // namespace sna
 
 using namespace sna;
+
+// ---- recorded launch lists ---------------------------------------------------------------------
+static hipError_t run_op(const PlanOp& op, hipStream_t s) {
+  const char* a = op.args.data();
+  switch (op.type) {
+    case PlanOp::IGEMM: return launch_igemm(*(const ConvGroupArgs*)a, op.variant, op.flag != 0, s);
+    case PlanOp::KREDUCE: return launch_splitk_reduce(*(const ConvGroupArgs*)a, s);
+    case PlanOp::DIRECT: return launch_direct_conv(*(const ConvGroupArgs*)a, op.flag, s);
+    case PlanOp::MAXPOOL: return launch_maxpool(*(const PoolGroupArgs*)a, op.flag, s);
+    case PlanOp::GAP: return launch_gap(*(const PoolGroupArgs*)a, op.flag, s);
+    case PlanOp::DW: return launch_depthwise(*(const DwGroupArgs*)a, s);
+    case PlanOp::SE: return launch_se(*(const SeGroupArgs*)a, s);
+    case PlanOp::LN: return launch_layernorm(*(const LnGroupArgs*)a, s);
+    case PlanOp::ATTN: return launch_attention(*(const AttnGroupArgs*)a, s);
+    case PlanOp::COPY: return launch_copy(*(const CopyArgs*)a, s);
+    case PlanOp::PAD: return launch_pad_input(*(const PadArgs*)a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// Calls f(byte offset) for every pointer field of the op's arguments that may point at a caller
+// buffer (activations in, results out; never weights or folded statistics).
+template <class F>
+static void visit_io_pointers(const PlanOp& op, F&& f) {
+  const char* base = op.args.data();
+  auto at = [&](const void* field) { f((int)((const char*)field - base)); };
+  switch (op.type) {
+    case PlanOp::IGEMM: case PlanOp::KREDUCE: case PlanOp::DIRECT: {
+      const ConvGroupArgs* a = (const ConvGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].res); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::MAXPOOL: case PlanOp::GAP: {
+      const PoolGroupArgs* a = (const PoolGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::DW: {
+      const DwGroupArgs* a = (const DwGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::SE: {
+      const SeGroupArgs* a = (const SeGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::LN: {
+      const LnGroupArgs* a = (const LnGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::ATTN: {
+      const AttnGroupArgs* a = (const AttnGroupArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].q); at(&a->p[i].k); at(&a->p[i].v); at(&a->p[i].o); }
+      break;
+    }
+    case PlanOp::COPY: { const CopyArgs* a = (const CopyArgs*)base; at(&a->src); at(&a->dst); break; }
+    case PlanOp::PAD: { const PadArgs* a = (const PadArgs*)base; at(&a->src); at(&a->dst); break; }
+  }
+}
+
+// Run a launch list on the stream, with the per-launch event brackets when timing is enabled.
+static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t stream) {
+  for (const PlanOp& op : plan.ops) {
+    hipEvent_t a = nullptr, b = nullptr;
+    if (net->prof_on) {
+      auto next_event = [&]() -> hipEvent_t {
+        if (net->ev_used == net->ev_pool.size()) {
+          hipEvent_t e;
+          if (hipEventCreate(&e) != hipSuccess) return nullptr;
+          net->ev_pool.push_back(e);
+        }
+        return net->ev_pool[net->ev_used++];
+      };
+      a = next_event(); b = next_event();
+      if (a && b && hipEventRecord(a, stream) != hipSuccess) a = b = nullptr;
+    }
+    const hipError_t e = run_op(op, stream);
+    if (e != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(e));
+    if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
+      net->prof_recs.push_back({op.kc, a, b});
+      net->prof_flops[op.kc] += op.flops;
+      net->prof_bytes[op.kc] += op.bytes;
+      net->prof_launches[op.kc] += 1;
+    }
+  }
+  net->last_macs = plan.macs;
+  net->last_launches = (int)plan.ops.size();
+  return SNA_OK;
+}
+
+constexpr size_t kMaxPlans = 64;
 
 extern "C" {
 
@@ -1014,16 +1100,44 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   if (((uintptr_t)inputs_dev | (uintptr_t)logits_dev) & 3) return fail(SNA_E_WORKSPACE, "inputs / logits must be 4-byte aligned");
   const ArchTables& T = net->T;
   const sna_arch_desc& a = T.arch;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (net->prof_on && net->prof_recs.size() > 200000) return fail(SNA_E_BATCH, "profile buffer full: call sna_profile_read");
+  for (int r = 0; r < n_requests; ++r)
+    if (req_cfg[r] < 0 || req_cfg[r] >= n_cfgs) return fail(SNA_E_BATCH, "req_cfg[%d]=%d outside [0, %d)", r, req_cfg[r], n_cfgs);
+
+  // The launch list depends on the routing, on the cfgs it names, on whether hidden states are
+  // wanted and on the tuning state; caller buffers only enter through patched pointer fields.
+  std::string key;
+  const bool use_cache = net->plan_cache_on && !net->tuning;
+  if (use_cache) {
+    key.reserve((size_t)n_requests * 4 + 1024);
+    const int32_t head[3] = {n_requests, hidden_dev ? 1 : 0, net->split_mode};
+    key.append((const char*)head, sizeof(head));
+    key.append((const char*)req_cfg, (size_t)n_requests * 4);
+    std::vector<char> seen(n_cfgs, 0);
+    for (int r = 0; r < n_requests; ++r)
+      if (!seen[req_cfg[r]]) {
+        seen[req_cfg[r]] = 1;
+        key.append((const char*)&cfgs[req_cfg[r]], sizeof(sna_subnet_cfg));
+      }
+    for (Plan& pl : net->plans)
+      if (pl.key == key) {
+        const void* bases[3] = {inputs_dev, logits_dev, hidden_dev};
+        for (const PlanPatch& pp : pl.patches)
+          *(const char**)(pl.ops[pp.op].args.data() + pp.offset) = (const char*)bases[pp.which] + pp.delta;
+        pl.last_use = ++net->plan_clock;
+        return execute_plan(net, pl, stream);
+      }
+  }
 
   Fwd f;
   f.net = net;
-  f.stream = (hipStream_t)hip_stream;
+  f.stream = stream;
   std::vector<int> gid(n_cfgs, -1);
   std::vector<size_t> req_off(n_requests), req_bytes(n_requests);
   size_t off = 0;
   for (int r = 0; r < n_requests; ++r) {
     const int ci = req_cfg[r];
-    if (ci < 0 || ci >= n_cfgs) return fail(SNA_E_BATCH, "req_cfg[%d]=%d outside [0, %d)", r, ci, n_cfgs);
     if (gid[ci] < 0) {
       sna_status st = validate_cfg(net, cfgs[ci]);
       if (st != SNA_OK) return st;
@@ -1056,7 +1170,6 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   }
   if ((size_t)(cur - net->arena) > net->arena_bytes) return fail(SNA_E_WORKSPACE, "arena overflow");
 
-  if (net->prof_on && net->prof_recs.size() > 200000) return fail(SNA_E_BATCH, "profile buffer full: call sna_profile_read");
   if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3) f.pad_inputs(inputs_dev, req_off);
   else f.bind_inputs(inputs_dev, req_off, req_bytes);
   sna_status st;
@@ -1069,9 +1182,37 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   }
   if (st != SNA_OK) return st;
   if (f.err != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(f.err));
-  net->last_macs = f.macs;
-  net->last_launches = f.launches;
-  return SNA_OK;
+
+  Plan plan;
+  plan.ops = std::move(f.ops);
+  plan.macs = f.macs;
+  // pointer fields that landed inside a caller buffer get rewritten when the list is replayed
+  const char* bases[3] = {(const char*)inputs_dev, (const char*)logits_dev, (const char*)hidden_dev};
+  const size_t extents[3] = {off, (size_t)n_requests * a.n_classes * sizeof(float),
+                             hidden_dev ? (size_t)n_requests * a.seq_len * a.hidden * T.esz : 0};
+  for (size_t i = 0; i < plan.ops.size(); ++i)
+    visit_io_pointers(plan.ops[i], [&](int offset) {
+      const char* v = *(const char* const*)(plan.ops[i].args.data() + offset);
+      for (int w = 0; w < 3; ++w)
+        if (bases[w] && v >= bases[w] && v < bases[w] + extents[w]) {
+          plan.patches.push_back({(int)i, offset, w, (size_t)(v - bases[w])});
+          break;
+        }
+    });
+  st = execute_plan(net, plan, stream);
+  if (st == SNA_OK && use_cache) {
+    plan.key = std::move(key);
+    plan.last_use = ++net->plan_clock;
+    if (net->plans.size() >= kMaxPlans) {                  // evict the least recently used list
+      size_t lru = 0;
+      for (size_t i = 1; i < net->plans.size(); ++i)
+        if (net->plans[i].last_use < net->plans[lru].last_use) lru = i;
+      net->plans[lru] = std::move(plan);
+    } else {
+      net->plans.push_back(std::move(plan));
+    }
+  }
+  return st;
 }
 
 sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t* launches) {
@@ -1091,6 +1232,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
                            void* hip_stream) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
   net->tuning = true;
+  net->plans.clear();                      // launch lists built before this call may use other tile variants
   sna_status st = sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
   net->tuning = false;
   if (st == SNA_OK && hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return fail(SNA_E_HIP, "stream synchronize");
@@ -1103,6 +1245,7 @@ sna_status sna_set_k_split(sna_supernet* net, int32_t mode) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
   if (mode < 0 || mode > 2) return fail(SNA_E_CFG_RANGE, "k split mode %d", mode);
   net->split_mode = mode;
+  net->plans.clear();
   return SNA_OK;
 }
 

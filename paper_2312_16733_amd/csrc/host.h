@@ -45,6 +45,25 @@ struct Group {
   int cur_buf = -1;
 };
 
+// One recorded kernel launch of a forward call.
+struct PlanOp {
+  enum Type { IGEMM, KREDUCE, DIRECT, MAXPOOL, GAP, DW, SE, LN, ATTN, COPY, PAD } type;
+  int variant = 0, flag = 0;         // igemm: tile variant, chunked kernel; direct / pool: dtype
+  int kc = 0;                        // kernel class for the per-launch timing
+  double flops = 0, bytes = 0;
+  std::vector<char> args;            // the launcher's argument struct
+};
+// A pointer field inside an op's arguments that points into a caller buffer of the forward call
+// (inputs, logits, hidden) rather than into the resident workspace: rewritten on every replay.
+struct PlanPatch { int op; int offset; int which; size_t delta; };
+struct Plan {
+  std::string key;                   // everything the launch list depends on, byte for byte
+  std::vector<PlanOp> ops;
+  std::vector<PlanPatch> patches;
+  int64_t macs = 0;
+  uint64_t last_use = 0;
+};
+
 }  // namespace sna
 
 struct sna_supernet {
@@ -63,6 +82,10 @@ struct sna_supernet {
   // measured for a chunked layer shape: 1 = one block per K chunk plus the reduction kernel is faster
   std::map<std::array<int, 6>, int> tuned_split;
   bool tuning = false;               // the forward in progress measures shapes it has no entry for
+  // launch lists of recent forward calls, replayed when the same cfgs / routing come again
+  std::vector<sna::Plan> plans;
+  uint64_t plan_clock = 0;
+  bool plan_cache_on = true;
   int n_subnets = 0, max_batch = 0;
   // bookkeeping of the last forward
   int64_t last_macs = 0;

@@ -472,3 +472,34 @@ def test_tuned_tile_variants_do_not_change_bits(torch_mod):
             check_parity(after[:1], oracle.forward(spec, W, S, c, x[:1]), "bf16", f"tuned cfg {ci}")
     finally:
         net.close()
+
+
+def test_replayed_launch_list_follows_the_callers_buffers(torch_mod, resnet_full):
+    """The second call with the same cfgs and routing replays a recorded launch list; inputs, logits
+    (and a different routing) must still be honoured."""
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    c = C[4]
+    xa = synth.make_inputs(spec, 3, c.in_h, c.in_w, 21)
+    xb = synth.make_inputs(spec, 3, c.in_h, c.in_w, 22)
+    r = np.zeros(3, np.int32)
+    da, db = to_dev(torch, spec, xa), to_dev(torch, spec, xb)
+    la = net.forward([c], r, da).cpu().numpy()          # builds the list
+    lb = net.forward([c], r, db).cpu().numpy()          # replays it on other buffers
+    la2 = net.forward([c], r, da).cpu().numpy()
+    np.testing.assert_array_equal(la, la2)
+    assert not np.array_equal(la, lb)
+    out = torch.zeros((3, spec.n_classes), dtype=torch.float32, device="cuda:0")
+    net.forward([c], r, db, logits=out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), lb)
+    # same cfg list, other routing: request 1 goes to another cfg of the same resolution
+    C2 = synth.enumerate_cfgs(spec, 16, 16733, fixed_res=c.in_h)
+    xa2 = synth.make_inputs(spec, 3, c.in_h, c.in_h, 21)
+    d2 = to_dev(torch, spec, xa2)
+    m1 = net.forward(C2, np.array([2, 5, 2], np.int32), d2).cpu().numpy()
+    m2 = net.forward(C2, np.array([2, 2, 5], np.int32), d2).cpu().numpy()
+    m1b = net.forward(C2, np.array([2, 5, 2], np.int32), d2).cpu().numpy()
+    np.testing.assert_array_equal(m1, m1b)
+    np.testing.assert_array_equal(m1[0], m2[0])
+    assert not np.array_equal(m1[1], m2[1])
