@@ -68,6 +68,8 @@ def main():
                     help="resnet = the headline workload (BASELINE config 2); the others are extra reports")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--save-tuning", action="store_true",
+                    help="measure every layer shape afresh and write the table the package ships")
     ap.add_argument("--no-tune", action="store_true",
                     help="skip the load-time measurement of tile variants per layer shape (heuristic choice only)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -113,14 +115,28 @@ def main():
 
     # load-time profiling, outside every timed region: each (cfg, batch) the run will serve is passed
     # through once with the library measuring its tile variants per layer shape
+    # Tile variants per layer shape: the table shipped with the package (measured on MI355X by
+    # `bench.py --save-tuning`) is loaded; whatever shape it lacks is measured now, outside every
+    # timed region, by passing each (cfg, batch) the run will serve through sna_subnet_tune once.
     t_tune = time.perf_counter()
+    table = os.path.join(os.path.dirname(os.path.abspath(sna.__file__)), "tuned", f"gfx950_{args.family}.txt")
+    n_loaded = 0
     if not args.no_tune:
+        if os.path.exists(table) and not args.save_tuning:
+            net.tuning_import(open(table).read())
+            n_loaded = net.tuned_count()
         detail_b = () if args.no_detail else ((1, 16, 64) if args.family != "transformer" else (1, 8, 32))
         for ci in range(n_cfgs):
             net.tune(cfgs_c[ci], route[:B], inputs[C[ci].in_h])
         for b in detail_b:
             for ci in (0, n_cfgs // 2, n_cfgs - 1):
                 net.tune(cfgs_c[ci], route[:b], inputs[C[ci].in_h])
+        if args.save_tuning:
+            os.makedirs(os.path.dirname(table), exist_ok=True)
+            with open(table, "w") as fh:
+                fh.write("# tile variant / K-split choices measured on MI355X by: python bench.py --family %s --save-tuning\n"
+                         % args.family)
+                fh.write(net.tuning_export())
     torch.cuda.synchronize()
     t_tune = time.perf_counter() - t_tune
 
@@ -195,7 +211,8 @@ def main():
                                   "one cfg per step",
                       "batch": B, "n_cfgs": n_cfgs,
                       "tile_variants": "heuristic" if args.no_tune else
-                                       f"measured per layer shape at load ({net.tuned_count()} entries, {t_tune:.1f} s, untimed)",
+                                       f"per layer shape: {n_loaded} entries from the shipped table, "
+                                       f"{net.tuned_count() - n_loaded} measured at load ({t_tune:.1f} s, untimed)",
                       "gmacs_per_image_range": [synth.subnet_macs(spec, C[0]) / 1e9,
                                                 synth.subnet_macs(spec, C[-1]) / 1e9],
                       "mean_gmacs_per_image": macs_total / (args.steps * B) / 1e9},

@@ -213,6 +213,16 @@ sna_status sna_subnet_tune(sna_supernet* net,
 /* Number of layer shapes with a measured tile variant on this handle. */
 int32_t sna_tuned_count(const sna_supernet* net);
 
+/* The measured choices as text, one per line ("v M K C RS stride parts variant" for a tile
+ * variant, "s M K C RS stride 0 flag" for the K-split decision), so that a deployment can ship
+ * them instead of measuring at every start.  Export writes at most `cap` bytes (host memory,
+ * NUL-terminated when it fits) and returns the size needed, excluding the NUL.  Import adds
+ * the lines of `text` (host memory, `len` bytes) to the handle's tables, replacing entries for
+ * the same shape; lines it cannot parse or that name an unknown variant give SNA_E_CFG_RANGE and
+ * nothing is imported.  Choices are hints: a wrong one costs time, never correctness. */
+int64_t sna_tuning_export(const sna_supernet* net, char* buf, int64_t cap);
+sna_status sna_tuning_import(sna_supernet* net, const char* text, int64_t len);
+
 void sna_supernet_free(sna_supernet* net);
 
 /* How long reductions are laid out over blocks.  A conv / linear whose reduction is

@@ -84,6 +84,8 @@ def lib():
     L.sna_subnet_forward.restype = i32
     L.sna_subnet_tune.argtypes = L.sna_subnet_forward.argtypes; L.sna_subnet_tune.restype = i32
     L.sna_tuned_count.argtypes = [vp]; L.sna_tuned_count.restype = i32
+    L.sna_tuning_export.argtypes = [vp, C.c_char_p, i64]; L.sna_tuning_export.restype = i64
+    L.sna_tuning_import.argtypes = [vp, C.c_char_p, i64]; L.sna_tuning_import.restype = i32
     L.sna_supernet_free.argtypes = [vp]; L.sna_supernet_free.restype = None
     L.sna_last_forward_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32)]; L.sna_last_forward_info.restype = i32
     L.sna_profile_enable.argtypes = [vp, i32]; L.sna_profile_enable.restype = i32
@@ -271,6 +273,16 @@ class Supernet:
 
     def tuned_count(self):
         return int(lib().sna_tuned_count(self.handle))
+
+    def tuning_export(self) -> str:
+        n = int(lib().sna_tuning_export(self.handle, None, 0))
+        buf = C.create_string_buffer(n + 1)
+        lib().sna_tuning_export(self.handle, buf, n + 1)
+        return buf.value.decode()
+
+    def tuning_import(self, text: str):
+        b = text.encode()
+        _check(lib().sna_tuning_import(self.handle, b, len(b)))
 
     def forward(self, cfgs, req_cfg, inputs, logits=None, hidden=None, stream=None, tune=False):
         """inputs: device tensor of the architecture's dtype, requests concatenated (flat is fine)."""

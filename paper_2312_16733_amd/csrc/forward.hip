@@ -1241,6 +1241,54 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
 
 int32_t sna_tuned_count(const sna_supernet* net) { return net ? (int32_t)(net->tuned.size() + net->tuned_split.size()) : 0; }
 
+int64_t sna_tuning_export(const sna_supernet* net, char* buf, int64_t cap) {
+  if (!net) return (int64_t)fail(SNA_E_NULL, "net is NULL");
+  std::string out;
+  char line[128];
+  for (const auto& kv : net->tuned) {
+    snprintf(line, sizeof(line), "v %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
+             kv.first[4], kv.first[5], kv.second);
+    out += line;
+  }
+  for (const auto& kv : net->tuned_split) {
+    snprintf(line, sizeof(line), "s %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
+             kv.first[4], kv.first[5], kv.second);
+    out += line;
+  }
+  if (buf && cap > 0) {
+    const size_t ncopy = std::min<size_t>(out.size(), (size_t)cap);
+    memcpy(buf, out.data(), ncopy);
+    if ((int64_t)out.size() < cap) buf[out.size()] = 0;
+  }
+  return (int64_t)out.size();
+}
+
+sna_status sna_tuning_import(sna_supernet* net, const char* text, int64_t len) {
+  if (!net || !text) return fail(SNA_E_NULL, "NULL argument");
+  std::map<std::array<int, 6>, int> tv, ts;
+  const std::string all(text, (size_t)(len < 0 ? 0 : len));
+  size_t pos = 0;
+  while (pos < all.size()) {
+    size_t end = all.find('\n', pos);
+    if (end == std::string::npos) end = all.size();
+    const std::string ln = all.substr(pos, end - pos);
+    pos = end + 1;
+    if (ln.empty() || ln[0] == '#') continue;
+    char kind = 0;
+    int k[6], val = 0;
+    if (sscanf(ln.c_str(), "%c %d %d %d %d %d %d %d", &kind, &k[0], &k[1], &k[2], &k[3], &k[4], &k[5], &val) != 8)
+      return fail(SNA_E_CFG_RANGE, "tuning line not understood: %s", ln.c_str());
+    const std::array<int, 6> key = {k[0], k[1], k[2], k[3], k[4], k[5]};
+    if (kind == 'v' && val >= 0 && val < igemm_num_variants()) tv[key] = val;
+    else if (kind == 's' && (val == 0 || val == 1)) ts[key] = val;
+    else return fail(SNA_E_CFG_RANGE, "tuning line out of range: %s", ln.c_str());
+  }
+  for (const auto& kv : tv) net->tuned[kv.first] = kv.second;
+  for (const auto& kv : ts) net->tuned_split[kv.first] = kv.second;
+  net->plans.clear();
+  return SNA_OK;
+}
+
 sna_status sna_set_k_split(sna_supernet* net, int32_t mode) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
   if (mode < 0 || mode > 2) return fail(SNA_E_CFG_RANGE, "k split mode %d", mode);
