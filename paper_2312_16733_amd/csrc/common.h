@@ -20,7 +20,8 @@ enum KClass {
   KC_COPY = 7,       // request gather / logits scatter
   KC_FOLD = 8,       // SubnetNorm statistics folding (load time)
   KC_KREDUCE = 9,    // sum of the K-chunk partials + fused epilogue of a split igemm
-  KC_COUNT = 10
+  KC_STEMPOOL = 10,  // fused 7x7/2 stem conv + SubnetNorm + ReLU + 3x3/2 max pool
+  KC_COUNT = 11
 };
 
 // ---- one problem of a grouped launch -------------------------------------------------------
@@ -113,6 +114,23 @@ struct AttnProblem {
 };
 struct AttnGroupArgs { int n; AttnProblem p[SNA_MAX_GROUPS]; };
 
+// fused ResNet stem (7x7 stride-2 conv, SubnetNorm, ReLU, 3x3 stride-2 max pool)
+struct StemPoolProblem {
+  const void* x;        // [N][H][W][8] channel-padded request images
+  const void* w;        // stem weights stored with 8 input channels, first tap of the 7x7 window
+  const float* scale; const float* shift;
+  void* y;              // [N][Po][Qo][K]
+  int N, H, W;
+  int Ho, Wo;           // conv output
+  int Po, Qo;           // pooled output
+  int K;                // active out channels (multiple of 8, <= 64)
+  int wk, wr, ws;       // element strides of the stored weight tensor
+  unsigned x_bytes;
+  int tiles_x, tiles_y; // pooled 4 x 16 tiles per image
+  int tile_start, tiles;
+};
+struct StemPoolArgs { int n; int total_tiles; StemPoolProblem p[SNA_MAX_GROUPS]; };
+
 struct CopyItem { unsigned long src, dst; unsigned long n; };   // byte offsets / length (even)
 #define SNA_COPY_ITEMS 128
 struct CopyArgs { const void* src; void* dst; int n; CopyItem it[SNA_COPY_ITEMS]; };
@@ -128,6 +146,7 @@ constexpr size_t kPartialBytes = (size_t)64 << 20;
 // ---- launchers (defined in the .hip files) ---------------------------------------------------
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s);
 hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s);
+hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s);
 void igemm_tile_shape(int variant, int* bm, int* bn);
 int igemm_num_variants();
 hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);

@@ -206,6 +206,9 @@ struct Fwd {
         ms /= reps;
         if (trial == 0 || ms < v_ms) v_ms = ms;
       }
+      if (getenv("SNA_TUNE_LOG"))
+        fprintf(stderr, "[tune] M=%d K=%d C=%d RS=%d stride=%d parts=%d chunked=%d variant %d: %.1f us\n", q.M, q.K, q.C,
+                q.R * q.S, q.stride, q.parts, (int)chunked, v, v_ms * 1e3);
       if (err == hipSuccess && (best < 0 || v_ms < *best_ms)) { best = v; *best_ms = v_ms; }
     }
     (void)hipEventDestroy(e0);
@@ -572,20 +575,56 @@ sna_status Fwd::run_tiny(const void*, float* logits) {
 sna_status Fwd::run_resnet(const void*, float* logits) {
   const sna_arch_desc& a = T().arch;
   for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = 8; }     // channel-padded inputs
-  conv_slot(false, [&](Group& g, ConvProblem& p) {
-    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
-    slice_conv(p, tensor("stem.w"), g.cfg->stage_out_ch[0], 7, 2);
-    p.c_count = a.in_ch;
-    p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
-    p.act = SNA_ACT_RELU; p.y = g.buf[0];
-    g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
-    return true;
-  });
-  pool_slot(true, [&](Group& g, PoolProblem& p) {
-    p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C; p.y = g.buf[1];
-    g.cur = p.y; g.cur_buf = 1; g.H = out_size(g.H, 3, 2); g.W = out_size(g.W, 3, 2);
-    return true;
-  });
+  bool fused_stem = a.dtype == SNA_DTYPE_BF16 && tensor("stem.w").dims[1] == 7 && tensor("stem.w").dims[2] == 7;
+  for (const Group& g : groups) fused_stem = fused_stem && g.cfg->stage_out_ch[0] <= 64;
+  if (fused_stem) {
+    // stem conv + SubnetNorm + ReLU + max pool in one kernel: the conv output stays in LDS
+    StemPoolArgs sa;
+    sa.n = 0;
+    int start = 0;
+    double flops = 0, bytes = 0;
+    for (Group& g : groups) {
+      ConvProblem c;
+      memset(&c, 0, sizeof(c));
+      c.N = g.n; c.H = g.H; c.W = g.W; c.C = g.C;
+      slice_conv(c, tensor("stem.w"), g.cfg->stage_out_ch[0], 7, 2);
+      StemPoolProblem p;
+      memset(&p, 0, sizeof(p));
+      p.x = g.cur; p.w = c.w; p.y = g.buf[1];
+      p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
+      p.N = g.n; p.H = g.H; p.W = g.W; p.Ho = c.Ho; p.Wo = c.Wo;
+      p.Po = out_size(c.Ho, 3, 2); p.Qo = out_size(c.Wo, 3, 2);
+      p.K = c.K; p.wk = c.wk; p.wr = c.wr; p.ws = c.ws; p.x_bytes = c.x_bytes;
+      p.tiles_x = (p.Qo + 15) / 16; p.tiles_y = (p.Po + 3) / 4;
+      p.tiles = p.N * p.tiles_x * p.tiles_y;
+      p.tile_start = start;
+      start += p.tiles;
+      sa.p[sa.n++] = p;
+      const double mac = (double)c.M * c.K * a.in_ch * 49;        // channel padding is not algorithmic work
+      macs += (int64_t)mac;
+      flops += 2 * mac;
+      bytes += 2.0 * ((double)g.n * g.H * g.W * a.in_ch + (double)c.K * 49 * a.in_ch) + 8.0 * c.K +
+               2.0 * (double)g.n * p.Po * p.Qo * c.K;
+      g.cur = p.y; g.cur_buf = 1; g.H = p.Po; g.W = p.Qo; g.C = c.K;
+    }
+    sa.total_tiles = start;
+    emit(PlanOp::STEMPOOL, 0, 0, KC_STEMPOOL, flops, bytes, sa);
+  } else {
+    conv_slot(false, [&](Group& g, ConvProblem& p) {
+      p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+      slice_conv(p, tensor("stem.w"), g.cfg->stage_out_ch[0], 7, 2);
+      p.c_count = a.in_ch;
+      p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
+      p.act = SNA_ACT_RELU; p.y = g.buf[0];
+      g.cur = p.y; g.cur_buf = 0; g.H = p.Ho; g.W = p.Wo; g.C = p.K;
+      return true;
+    });
+    pool_slot(true, [&](Group& g, PoolProblem& p) {
+      p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C; p.y = g.buf[1];
+      g.cur = p.y; g.cur_buf = 1; g.H = out_size(g.H, 3, 2); g.W = out_size(g.W, 3, 2);
+      return true;
+    });
+  }
   // buffers: block input lives in buf[0] or buf[1]; buf[2] conv1 out, buf[3] conv2 out, buf[4] shortcut
   for (int s = 0; s < a.n_stages; ++s)
     for (int j = 0; j < a.stage_max_depth[s]; ++j) {
@@ -910,6 +949,7 @@ static hipError_t run_op(const PlanOp& op, hipStream_t s) {
     case PlanOp::ATTN: return launch_attention(*(const AttnGroupArgs*)a, s);
     case PlanOp::COPY: return launch_copy(*(const CopyArgs*)a, s);
     case PlanOp::PAD: return launch_pad_input(*(const PadArgs*)a, s);
+    case PlanOp::STEMPOOL: return launch_stem_pool(*(const StemPoolArgs*)a, s);
   }
   return hipErrorInvalidValue;
 }
@@ -953,6 +993,11 @@ static void visit_io_pointers(const PlanOp& op, F&& f) {
     }
     case PlanOp::COPY: { const CopyArgs* a = (const CopyArgs*)base; at(&a->src); at(&a->dst); break; }
     case PlanOp::PAD: { const PadArgs* a = (const PadArgs*)base; at(&a->src); at(&a->dst); break; }
+    case PlanOp::STEMPOOL: {
+      const StemPoolArgs* a = (const StemPoolArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
   }
 }
 
@@ -1224,7 +1269,7 @@ sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t
 
 static const char* kClassNames[SNA_N_KCLASS] = {"igemm_conv_linear", "direct_conv", "depthwise", "pool",
                                                 "squeeze_excite", "layernorm", "attention", "copy",
-                                                "fold_stats", "k_chunk_reduce", "", ""};
+                                                "fold_stats", "k_chunk_reduce", "stem_pool", ""};
 const char* sna_profile_class_name(int32_t k) { return (k >= 0 && k < SNA_N_KCLASS) ? kClassNames[k] : ""; }
 
 sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs, const int32_t* req_cfg,

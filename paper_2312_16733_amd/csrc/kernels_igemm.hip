@@ -67,7 +67,9 @@ __device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
 
 // Waves per SIMD the register allocation must leave room for: tiles with short reductions are
 // launched with a small LDS request and then run that many blocks per CU.
-constexpr int igemm_min_waves(int bm, int bn) { return bm * bn >= 128 * 128 ? 3 : (bm * bn >= 128 * 96 ? 4 : 5); }
+constexpr int igemm_min_waves(int bm, int bn) {
+  return bm * bn > 128 * 128 ? 2 : (bm * bn >= 128 * 128 ? 3 : (bm * bn >= 128 * 96 ? 4 : 5));
+}
 
 // WS (wave-specialised): the block has twice the waves; the second half only fetches (address
 // arithmetic, global->LDS loads, the wait for them), the first half only computes, and the two
@@ -75,7 +77,8 @@ constexpr int igemm_min_waves(int bm, int bn) { return bm * bn >= 128 * 128 ? 3 
 // holds up MFMA issue, which matters when a CU has a single block to overlap with itself.
 template <int BM, int BN, int WARPS_M, int WARPS_N, int NS, bool CHUNKED, bool WS>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * (WS ? 2 : 1),
-                             WS ? (BM * BN >= 128 * 128 ? 2 : 4) : (CHUNKED ? (BM * BN == 128 * 64 ? 3 : 2) : igemm_min_waves(BM, BN)))
+                             WS ? (BM * BN >= 128 * 128 ? 2 : 4)
+                                : (CHUNKED ? (BM * BN == 128 * 64 ? 3 : (BM * BN > 128 * 128 ? 1 : 2)) : igemm_min_waves(BM, BN)))
 void igemm_kernel(const ConvGroupArgs args) {
 #if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
   using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N, NS>;
@@ -531,11 +534,13 @@ static const Variant kVariants[] = {
     SNA_VARIANT(32, 128, 1, 4, 4),
     SNA_WS_VARIANT(64, 64, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 3), SNA_WS_VARIANT(128, 64, 2, 2, 3),
     SNA_WS_VARIANT(128, 96, 4, 1, 3), SNA_WS_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 32, 4, 1, 2),
-    SNA_WS_VARIANT(32, 128, 1, 4, 4),
+    SNA_WS_VARIANT(32, 128, 1, 4, 4), SNA_VARIANT(128, 192, 2, 2, 2), SNA_WS_VARIANT(128, 192, 2, 2, 3),
 #ifdef SNA_EXTRA_VARIANTS
     SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
     SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 4),
     SNA_WS_VARIANT(128, 64, 2, 2, 2), SNA_WS_VARIANT(64, 128, 1, 4, 2),
+    SNA_VARIANT(256, 128, 2, 2, 2), SNA_WS_VARIANT(256, 128, 2, 2, 3),
+    SNA_WS_VARIANT(128, 192, 2, 2, 2), SNA_WS_VARIANT(256, 128, 2, 2, 2), SNA_WS_VARIANT(256, 128, 4, 1, 3),
 #endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
