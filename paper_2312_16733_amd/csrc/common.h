@@ -163,12 +163,15 @@ hipError_t launch_fold_stats(const float* stats, float* folded, int n_subnets, l
 // ---- device helpers ---------------------------------------------------------------------------
 #if defined(__HIPCC__)
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
-// round-to-nearest-even; inputs are finite
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  unsigned u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// round-to-nearest-even through the hardware conversion (v_cvt_pk_bf16_f32); checked bit for bit
+// against the integer formulation on all finite patterns
+typedef __bf16 sna_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float sna_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  const sna_f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, sna_bf16x2));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 __device__ __forceinline__ float apply_act(float v, int act) {
   if (act == SNA_ACT_RELU) return fmaxf(v, 0.f);
   if (act == SNA_ACT_HSWISH) return v * fminf(fmaxf(v + 3.f, 0.f), 6.f) * (1.f / 6.f);

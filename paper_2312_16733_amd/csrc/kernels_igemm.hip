@@ -399,10 +399,10 @@ void igemm_kernel(const ConvGroupArgs args) {
             *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
           } else {
             uint4 o;
-            o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
-            o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
-            o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
-            o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
+            o.x = pack_bf16x2(val[0], val[1]);
+            o.y = pack_bf16x2(val[2], val[3]);
+            o.z = pack_bf16x2(val[4], val[5]);
+            o.w = pack_bf16x2(val[6], val[7]);
             *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
           }
         }
@@ -506,10 +506,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvGroupArgs 
     *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
   } else {
     uint4 o;
-    o.x = (unsigned)f32_to_bf16(val[0]) | ((unsigned)f32_to_bf16(val[1]) << 16);
-    o.y = (unsigned)f32_to_bf16(val[2]) | ((unsigned)f32_to_bf16(val[3]) << 16);
-    o.z = (unsigned)f32_to_bf16(val[4]) | ((unsigned)f32_to_bf16(val[5]) << 16);
-    o.w = (unsigned)f32_to_bf16(val[6]) | ((unsigned)f32_to_bf16(val[7]) << 16);
+    o.x = pack_bf16x2(val[0], val[1]);
+    o.y = pack_bf16x2(val[2], val[3]);
+    o.z = pack_bf16x2(val[4], val[5]);
+    o.w = pack_bf16x2(val[6], val[7]);
     *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
   }
 }

@@ -195,8 +195,8 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
           const float v2 = fmaxf(fmaf(acc[i][j][4 * gq + 2], sc[j][gq].z, sh[j][gq].z), 0.f);
           const float v3 = fmaxf(fmaf(acc[i][j][4 * gq + 3], sc[j][gq].w, sh[j][gq].w), 0.f);
           uint2 o;
-          o.x = valid ? ((unsigned)f32_to_bf16(v0) | ((unsigned)f32_to_bf16(v1) << 16)) : 0xFF80FF80u;   // -inf pads the pool
-          o.y = valid ? ((unsigned)f32_to_bf16(v2) | ((unsigned)f32_to_bf16(v3) << 16)) : 0xFF80FF80u;
+          o.x = valid ? (pack_bf16x2(v0, v1)) : 0xFF80FF80u;   // -inf pads the pool
+          o.y = valid ? (pack_bf16x2(v2, v3)) : 0xFF80FF80u;
           *(uint2*)(sout + sp * SOUT_ROW_B + ch * 2) = o;
         }
       }

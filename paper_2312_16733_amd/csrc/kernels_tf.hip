@@ -181,10 +181,10 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const LnGroupArgs args) 
 #pragma unroll
       for (int e = 0; e < 8; ++e) r[e] = fmaf((v[i][e] - mean) * rstd, p.gamma[o * 8 + e], p.beta[o * 8 + e]);
       uint4 out;
-      out.x = (unsigned)f32_to_bf16(r[0]) | ((unsigned)f32_to_bf16(r[1]) << 16);
-      out.y = (unsigned)f32_to_bf16(r[2]) | ((unsigned)f32_to_bf16(r[3]) << 16);
-      out.z = (unsigned)f32_to_bf16(r[4]) | ((unsigned)f32_to_bf16(r[5]) << 16);
-      out.w = (unsigned)f32_to_bf16(r[6]) | ((unsigned)f32_to_bf16(r[7]) << 16);
+      out.x = pack_bf16x2(r[0], r[1]);
+      out.y = pack_bf16x2(r[2], r[3]);
+      out.z = pack_bf16x2(r[4], r[5]);
+      out.w = pack_bf16x2(r[6], r[7]);
       *(uint4*)(y + o * 8) = out;
     }
   }
