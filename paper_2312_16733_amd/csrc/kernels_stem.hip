@@ -71,6 +71,16 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     pbase[i] = ((2 * sy) * IW + sx) * 16;
   }
 
+  // which input pixel of a patch each of this thread's DMA lanes fetches (the same for every tile)
+  int lane_yx[PASSES];
+#pragma unroll
+  for (int pass = 0; pass < PASSES; ++pass) {
+    const int i = pass * 256 + tid;
+    const int iy = i / IW, qq = i - iy * IW;                 // slot qq of a row: even columns, then odd columns
+    const int ix = qq < IWE ? 2 * qq : 2 * (qq - IWE) + 1;
+    lane_yx[pass] = i < NIP ? (iy << 16) | ix : -1;
+  }
+
   // Request the input patch of a tile: global -> LDS, 16 bytes per lane, zeros outside the image.
   auto request_patch = [&](int t) {
     const int gp = find_problem(args, t);
@@ -84,11 +94,8 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)q.x, 0, (int)q.x_bytes, 0x00020000);
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
-      const int i = pass * 256 + tid;
-      const int iy = i / IW, qq = i - iy * IW;               // slot qq of a row: even columns, then odd columns
-      const int ix = qq < IWE ? 2 * qq : 2 * (qq - IWE) + 1;
-      const int gy = iy0 + iy, gx = ix0 + ix;
-      const bool ok = i < NIP && gy >= 0 && gy < q.H && gx >= 0 && gx < q.W;
+      const int gy = iy0 + (lane_yx[pass] >> 16), gx = ix0 + (lane_yx[pass] & 0xffff);
+      const bool ok = lane_yx[pass] >= 0 && gy >= 0 && gy < q.H && gx >= 0 && gx < q.W;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_char*)patch + (pass * 256 + wave * 64) * 16, 16,
                                                ok ? (unsigned)(((n * q.H + gy) * q.W + gx) * 16) : OOB, 0, 0, 0);
     }
@@ -195,8 +202,10 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
           const float v2 = fmaxf(fmaf(acc[i][j][4 * gq + 2], sc[j][gq].z, sh[j][gq].z), 0.f);
           const float v3 = fmaxf(fmaf(acc[i][j][4 * gq + 3], sc[j][gq].w, sh[j][gq].w), 0.f);
           uint2 o;
-          o.x = valid ? (pack_bf16x2(v0, v1)) : 0xFF80FF80u;   // -inf pads the pool
-          o.y = valid ? (pack_bf16x2(v2, v3)) : 0xFF80FF80u;
+          // after the ReLU every value is >= 0: with the sign bit cleared (-0 -> +0) bf16 order is
+          // unsigned 16-bit order, and 0 can stand in for the pool's -inf padding
+          o.x = valid ? (pack_bf16x2(v0, v1) & 0x7fff7fffu) : 0u;
+          o.y = valid ? (pack_bf16x2(v2, v3) & 0x7fff7fffu) : 0u;
           *(uint2*)(sout + sp * SOUT_ROW_B + ch * 2) = o;
         }
       }
@@ -210,9 +219,10 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
       const int ly = pp / PW, lx = pp - ly * PW;
       const int py = py0 + ly, px = px0 + lx;
       if (py >= p.Po || px >= p.Qo) continue;
-      float best[8];
+      typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+      u16x2 best[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) best[e] = -3.0e38f;
+      for (int e = 0; e < 4; ++e) best[e] = u16x2{0, 0};
 #pragma unroll
       for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
@@ -220,16 +230,11 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
           const uint4 v = *(const uint4*)(sout + ((2 * ly + dy) * SW + 2 * lx + dx) * SOUT_ROW_B + oct * 16);
           const unsigned u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            best[2 * e] = fmaxf(best[2 * e], __uint_as_float(u[e] << 16));
-            best[2 * e + 1] = fmaxf(best[2 * e + 1], __uint_as_float(u[e] & 0xffff0000u));
-          }
+          for (int e = 0; e < 4; ++e) best[e] = __builtin_elementwise_max(best[e], __builtin_bit_cast(u16x2, u[e]));
         }
       uint4 o;
-      unsigned* ou = (unsigned*)&o;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)       // the operands are bf16 values: the max needs no rounding
-        ou[e] = (__float_as_uint(best[2 * e]) >> 16) | (__float_as_uint(best[2 * e + 1]) & 0xffff0000u);
+      o.x = __builtin_bit_cast(unsigned, best[0]); o.y = __builtin_bit_cast(unsigned, best[1]);
+      o.z = __builtin_bit_cast(unsigned, best[2]); o.w = __builtin_bit_cast(unsigned, best[3]);
       *(uint4*)((bf16_t*)p.y + (((long)n * p.Po + py) * p.Qo + px) * K + oct * 8) = o;
     }
     __syncthreads();                                         // sout and w_lds free for the next tile
