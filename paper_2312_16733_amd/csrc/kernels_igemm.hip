@@ -97,8 +97,13 @@ void igemm_kernel(const ConvGroupArgs args) {
   const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile_id >= args.total_tiles) return;
 
-  const int g = find_problem(args, tile_id);
-  const ConvProblem p = args.p[g];         // by value: uniform fields live in SGPRs across the asm blocks
+  // by value: uniform fields live in SGPRs across the asm blocks.  The first problem's descriptor sits at
+  // a fixed kernarg offset, so its load does not wait for the problem search (most launches carry one).
+  ConvProblem p = args.p[0];
+  if (args.n > 1) {
+    const int g = find_problem(args, tile_id);
+    if (g > 0) p = args.p[g];
+  }
   int local = tile_id - p.tile_start;
   int part = 0;                            // which K range of the problem this block reduces over
   if (p.parts > 1) {
