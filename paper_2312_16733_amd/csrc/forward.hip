@@ -227,7 +227,7 @@ struct Fwd {
     return (kt_all + n - 1) / n;
   }
 
-  void run_igemm(std::vector<ConvProblem>& ps) {
+  void run_igemm(std::vector<ConvProblem>& ps, bool unify = false) {
     if (ps.empty()) return;
     const size_t n = ps.size();
     std::vector<int> var(n), chunks(n);
@@ -293,6 +293,21 @@ struct Fwd {
       auto it = net->tuned.find(tune_key(q, q.parts));
       if (it != net->tuned.end()) var[i] = it->second;
       place(q, var[i]);
+    }
+    if (unify && !net->tuning) {
+      // one variant per kernel flavour: that of the problem with the most work
+      for (int chunked = 0; chunked < 2; ++chunked) {
+        int lead = -1;
+        double lead_work = -1;
+        for (size_t i = 0; i < n; ++i) {
+          if ((ps[i].parts == 1 && chunks[i] > 1) != (chunked == 1)) continue;
+          const double work = (double)ps[i].M * ps[i].K * (ps[i].C * ps[i].R * ps[i].S + 64.0);
+          if (work > lead_work) { lead_work = work; lead = (int)i; }
+        }
+        if (lead < 0) continue;
+        for (size_t i = 0; i < n; ++i)
+          if ((ps[i].parts == 1 && chunks[i] > 1) == (chunked == 1)) { var[i] = var[lead]; place(ps[i], var[i]); }
+      }
     }
     if (err != hipSuccess) return;
     for (int chunked = 0; chunked < 2; ++chunked)
@@ -374,6 +389,27 @@ struct Fwd {
       if (fill(g, p)) ps.push_back(p);
     }
     if (direct) run_direct(ps); else run_igemm(ps);
+  }
+
+  // Two layers that read the same input and do not depend on each other (a stage's conv1 and its
+  // projection shortcut) go into one grouped launch: they share one tile variant, the one chosen for
+  // the layer with more work, and the second launch with its fixed cost disappears.
+  void conv_slot2(const std::function<bool(Group&, ConvProblem&)>& fill_a,
+                  const std::function<bool(Group&, ConvProblem&)>& fill_b) {
+    std::vector<ConvProblem> ps;
+    for (int which = 0; which < 2; ++which)
+      for (Group& g : groups) {
+        ConvProblem p;
+        memset(&p, 0, sizeof(p));
+        if ((which == 0 ? fill_a : fill_b)(g, p)) ps.push_back(p);
+      }
+    if (ps.size() > SNA_MAX_GROUPS) {      // would not fit one launch anyway
+      std::vector<ConvProblem> a(ps.begin(), ps.begin() + ps.size() / 2), b(ps.begin() + ps.size() / 2, ps.end());
+      run_igemm(a);
+      run_igemm(b);
+      return;
+    }
+    run_igemm(ps, true);
   }
 
   void pool_slot(bool is_max, const std::function<bool(Group&, PoolProblem&)>& fill) {
@@ -631,14 +667,25 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
       const std::string pre = "s" + std::to_string(s) + ".b" + std::to_string(j) + ".";
       const int st = j == 0 ? a.stage_stride[s] : 1;
       auto on = [&](const Group& g) { return j < g.cfg->depth[s]; };
-      conv_slot(false, [&](Group& g, ConvProblem& p) {
+      auto conv1 = [&](Group& g, ConvProblem& p) {
         if (!on(g)) return false;
         p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
         slice_conv(p, tensor(pre + "conv1.w"), g.cfg->block_mid_ch[s][j], 1, 1);
         p.scale = scale_of(pre + "sn1", g.cfg->subnet_id); p.shift = shift_of(pre + "sn1", g.cfg->subnet_id);
         p.act = SNA_ACT_RELU; p.y = g.buf[2];
         return true;
-      });
+      };
+      auto shortcut = [&](Group& g, ConvProblem& p) {
+        if (!on(g)) return false;
+        p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
+        slice_conv(p, tensor(pre + "short.w"), g.cfg->stage_out_ch[1 + s], 1, st);
+        p.scale = scale_of(pre + "sn_short", g.cfg->subnet_id);
+        p.shift = shift_of(pre + "sn_short", g.cfg->subnet_id);
+        p.act = SNA_ACT_NONE; p.y = g.buf[4];
+        return true;
+      };
+      if (j == 0) conv_slot2(conv1, shortcut);
+      else conv_slot(false, conv1);
       conv_slot(false, [&](Group& g, ConvProblem& p) {
         if (!on(g)) return false;
         const int m = g.cfg->block_mid_ch[s][j];
@@ -648,16 +695,6 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
         p.act = SNA_ACT_RELU; p.y = g.buf[3];
         return true;
       });
-      if (j == 0)
-        conv_slot(false, [&](Group& g, ConvProblem& p) {
-          if (!on(g)) return false;
-          p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
-          slice_conv(p, tensor(pre + "short.w"), g.cfg->stage_out_ch[1 + s], 1, st);
-          p.scale = scale_of(pre + "sn_short", g.cfg->subnet_id);
-          p.shift = shift_of(pre + "sn_short", g.cfg->subnet_id);
-          p.act = SNA_ACT_NONE; p.y = g.buf[4];
-          return true;
-        });
       conv_slot(false, [&](Group& g, ConvProblem& p) {
         if (!on(g)) return false;
         const int m = g.cfg->block_mid_ch[s][j];
