@@ -503,3 +503,34 @@ def test_replayed_launch_list_follows_the_callers_buffers(torch_mod, resnet_full
     np.testing.assert_array_equal(m1, m1b)
     np.testing.assert_array_equal(m1[0], m2[0])
     assert not np.array_equal(m1[1], m2[1])
+
+
+def test_tuning_table_round_trip_and_rejects_bad_lines(torch_mod):
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    spec = synth.ResNetSpec()
+    W, S, C = setup(spec, 16)
+    net = sna.Supernet(spec, W, S, 16, 8)
+    other = sna.Supernet(spec, W, S, 16, 8)
+    try:
+        c = C[6]
+        x = synth.make_inputs(spec, 2, c.in_h, c.in_w, 23)
+        net.tune([c], np.zeros(2, np.int32), to_dev(torch, spec, x))
+        torch.cuda.synchronize()
+        text = net.tuning_export()
+        lines = [ln for ln in text.splitlines() if ln]
+        assert len(lines) == net.tuned_count() and all(ln[0] in "vs" and len(ln.split()) == 8 for ln in lines)
+        other.tuning_import("# comment\n" + text)
+        assert other.tuned_count() == net.tuned_count()
+        assert sorted(other.tuning_export().splitlines()) == sorted(lines)
+        a = run_single(torch, net, spec, c, x)
+        b = run_single(torch, other, spec, c, x)
+        np.testing.assert_array_equal(a, b)
+        n0 = other.tuned_count()
+        for bad in ("v 1 2 3\n", "v 64 64 64 1 1 1 999\n", "x 1 2 3 4 5 6 0\n", "s 1 2 3 4 5 0 7\n"):
+            with pytest.raises(sna.SnaError):
+                other.tuning_import(text + bad)
+            assert other.tuned_count() == n0
+    finally:
+        net.close()
+        other.close()
