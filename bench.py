@@ -199,6 +199,24 @@ def main():
                 detail[f"b{b}_{tag}"] = {"images_per_s": b / d, "ms": d * 1e3,
                                          "gmacs_per_image": synth.subnet_macs(spec, C[ci]) / 1e9}
 
+        if args.family == "resnet":
+            # BASELINE config 4: one call that mixes the cfgs, 64 requests routed Zipf(1.1) over them
+            Cm = synth.enumerate_cfgs(spec, n_cfgs, 16733, fixed_res=224)
+            routem = synth.zipf_assignment(64, n_cfgs, 4)
+            xm = torch.from_numpy(synth.make_inputs(spec, 64, 224, 224, 13)).to(torch.bfloat16).to(dev)
+            cm = net.prepare_cfgs(Cm)
+            for i in range(3):
+                net.forward(cm, routem, xm, logits=logits)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for i in range(20):
+                net.forward(cm, routem, xm, logits=logits)
+            torch.cuda.synchronize()
+            d = (time.perf_counter() - t1) / 20
+            detail["mixed64_zipf_res224"] = {"images_per_s": 64 / d, "ms": d * 1e3,
+                                             "distinct_cfgs": int(len(set(routem.tolist()))),
+                                             "launches": net.last_forward_info()[1]}
+
     out = {"metric": "subnet images/s at batch 64 across the subnet range", "value": value,
            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",

@@ -294,8 +294,10 @@ struct Fwd {
       if (it != net->tuned.end()) var[i] = it->second;
       place(q, var[i]);
     }
-    if (unify && !net->tuning) {
-      // one variant per kernel flavour: that of the problem with the most work
+    if ((unify || n > 1) && !net->tuning) {
+      // several problems in one slot (a mixed batch, or two layers sharing a launch): every extra tile
+      // variant is an extra launch with its fixed cost, so there is one variant per kernel flavour,
+      // that of the problem with the most work
       for (int chunked = 0; chunked < 2; ++chunked) {
         int lead = -1;
         double lead_work = -1;
