@@ -68,10 +68,16 @@ struct ConvGroupArgs {
   ConvProblem p[SNA_MAX_GROUPS];
 };
 
+// Global average pool ahead of a squeeze-excite gate: the pixels of a request are cut into up to
+// SNA_GAP_MAX_SEGS segments (a function of H*W only) summed by different blocks; the gate adds the
+// segment sums in order.
+#define SNA_GAP_MAX_SEGS 8
+
 struct PoolProblem {    // max pool 3x3/2 or global average pool
   const void* x; void* y;
   int N, H, W, C, Ho, Wo;
   int out_fp32;         // global average pool only: write fp32 instead of the storage dtype
+  int segs;             // global average pool only: > 1 = write fp32 segment sums [segs][N][C], not the mean
   int tile_start, tiles;
 };
 struct PoolGroupArgs { int n; PoolProblem p[SNA_MAX_GROUPS]; };
@@ -91,11 +97,13 @@ struct SeProblem {
   void* y;              // gated output (may alias x)
   const void* w1; const float* b1;  // [Q_max][C_max] stored; leading [Q][C] used
   const void* w2; const float* b2;  // [C_max][Q_max]
-  float* pooled;        // [N][C] scratch
+  float* pooled;        // [pool_segs][N][C] segment sums of the pool (the mean when pool_segs == 1)
   float* gate;          // [N][C] scratch
   float* hidden;        // [N][Q] scratch
   int N, HW, C, Q;
   int w1_stride, w2_stride;
+  int pool_segs;        // > 1: pooled holds sums, scaled by inv_hw here
+  float inv_hw;
   int tile_start, tiles;
 };
 struct SeGroupArgs { int n; SeProblem p[SNA_MAX_GROUPS]; };

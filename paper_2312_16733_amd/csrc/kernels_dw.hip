@@ -153,7 +153,17 @@ __global__ __launch_bounds__(256) void se_fc_kernel(const SeGroupArgs args) {
     for (int i8 = lane; i8 < (I >> 3); i8 += 64) {
       float wv[8];
       unpack8(*(const uint4*)(w + (long)o * ws + i8 * 8), wv);
-      const float4 x0 = *(const float4*)(in + i8 * 8), x1 = *(const float4*)(in + i8 * 8 + 4);
+      float4 x0 = *(const float4*)(in + i8 * 8), x1 = *(const float4*)(in + i8 * 8 + 4);
+      if (!HSIG && p.pool_segs > 1) {           // the pool left segment sums: add them in order, then scale
+        for (int sgm = 1; sgm < p.pool_segs; ++sgm) {
+          const float* ins = in + (long)sgm * p.N * I;
+          const float4 y0 = *(const float4*)(ins + i8 * 8), y1 = *(const float4*)(ins + i8 * 8 + 4);
+          x0.x += y0.x; x0.y += y0.y; x0.z += y0.z; x0.w += y0.w;
+          x1.x += y1.x; x1.y += y1.y; x1.z += y1.z; x1.w += y1.w;
+        }
+        x0.x *= p.inv_hw; x0.y *= p.inv_hw; x0.z *= p.inv_hw; x0.w *= p.inv_hw;
+        x1.x *= p.inv_hw; x1.y *= p.inv_hw; x1.z *= p.inv_hw; x1.w *= p.inv_hw;
+      }
       a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
       a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
     }

@@ -162,7 +162,7 @@ sna_status build_tables(const sna_arch_desc* a, ArchTables* t) {
         b.conv(p + "project.w", c, 1, m); b.norm(p + "sn3", c);
         upd((int64_t)(j == 0 ? h : ho) * (j == 0 ? h : ho) * m);
         upd((int64_t)ho * ho * (m > c ? m : c));
-        if (2 * m + q > small) small = 2 * m + q;
+        if ((SNA_GAP_MAX_SEGS + 1) * m + q > small) small = (SNA_GAP_MAX_SEGS + 1) * m + q;   // pooled partials, gate, hidden
       }
       h = ho; prev = c;
     }
