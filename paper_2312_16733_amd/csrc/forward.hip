@@ -416,7 +416,7 @@ struct Fwd {
 
   // segments of the squeeze-excite pool: by image size only, so that a request's sum order is fixed
   static int gap_segs(int hw) {
-    const int s = hw / 256;
+    const int s = hw / 64;
     return s < 1 ? 1 : (s > SNA_GAP_MAX_SEGS ? SNA_GAP_MAX_SEGS : s);
   }
 

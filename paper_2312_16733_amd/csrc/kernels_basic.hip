@@ -200,6 +200,7 @@ __global__ __launch_bounds__(256) void gap_kernel(const PoolGroupArgs args) {
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   if (cv < cvn) {
     const T* x = (const T*)p.x + (long)n * HW * p.C + cv * VEC;
+#pragma unroll 4
     for (int h = h_begin + hl; h < h_end; h += 8) {
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[i] += ld_f32<T>(x + (long)h * p.C + i);
