@@ -49,6 +49,13 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) 
   constexpr int PAD = K / 2;
   const bf16_t* x = (const bf16_t*)p.x + (long)n * p.H * p.W * p.C + c8 * 8;
   const bf16_t* w = (const bf16_t*)p.w + c8 * 8;           // already at the centre window's first tap
+  // The taps of a kernel row are taken two at a time with v_dot2_f32_bf16: per channel one register
+  // holds (x[col], x[col + 1]) and one (w[s], w[s + 1]), built from the channel-pair words of memory with
+  // byte permutes; no bf16 -> fp32 unpacking and half the multiply-add instructions.  An odd last tap
+  // is paired with a zero weight.
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  constexpr int WP = (K + 1) / 2;                          // tap pairs per kernel row
+  constexpr int CSTEP = STRIDE == 2 ? 2 : 1;                 // stride 2 only ever pairs (even, odd) columns
   float acc[DW_TW][8];
 #pragma unroll
   for (int o = 0; o < DW_TW; ++o)
@@ -59,21 +66,52 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) 
   for (int r = 0; r < K; ++r) {
     const int ih = pp * STRIDE + r - PAD;
     if (ih < 0 || ih >= p.H) continue;
-    float col[COLS][8];                   // this kernel row's input columns, converted once
+    uint4 raw[COLS + 1];
 #pragma unroll
     for (int cidx = 0; cidx < COLS; ++cidx) {
       const int iw = iw0 + cidx;
-      const uint4 v = (iw >= 0 && iw < p.W) ? *(const uint4*)(x + ((long)ih * p.W + iw) * p.C) : make_uint4(0, 0, 0, 0);
-      unpack8(v, col[cidx]);
+      raw[cidx] = (iw >= 0 && iw < p.W) ? *(const uint4*)(x + ((long)ih * p.W + iw) * p.C) : make_uint4(0, 0, 0, 0);
+    }
+    raw[COLS] = make_uint4(0, 0, 0, 0);
+    unsigned wp[WP][8];                    // [tap pair][channel]: (w[2t], w[2t + 1])
+#pragma unroll
+    for (int t = 0; t < WP; ++t) {
+      const uint4 w0 = *(const uint4*)(w + (long)r * p.wr + (long)(2 * t) * p.ws);
+      const uint4 w1 = 2 * t + 1 < K ? *(const uint4*)(w + (long)r * p.wr + (long)(2 * t + 1) * p.ws) : make_uint4(0, 0, 0, 0);
+      const unsigned a0[4] = {w0.x, w0.y, w0.z, w0.w}, a1[4] = {w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        wp[t][2 * d] = __builtin_amdgcn_perm(a1[d], a0[d], 0x05040100u);
+        wp[t][2 * d + 1] = __builtin_amdgcn_perm(a1[d], a0[d], 0x07060302u);
+      }
     }
 #pragma unroll
-    for (int s = 0; s < K; ++s) {
-      float wv[8];
-      unpack8(*(const uint4*)(w + (long)r * p.wr + (long)s * p.ws), wv);
+    for (int c = 0; c < COLS; c += CSTEP) {
+      // is this column pair the start of a tap pair of some output?  (c = o * STRIDE + 2 t)
+      bool used = false;
 #pragma unroll
       for (int o = 0; o < DW_TW; ++o)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(col[o * STRIDE + s][e], wv[e], acc[o][e]);
+        for (int t = 0; t < WP; ++t) used = used || (c == o * STRIDE + 2 * t);
+      if (!used) continue;
+      const unsigned x0[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
+      const unsigned x1[4] = {raw[c + 1].x, raw[c + 1].y, raw[c + 1].z, raw[c + 1].w};
+      unsigned xp[8];                      // [channel]: (x[col c], x[col c + 1])
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        xp[2 * d] = __builtin_amdgcn_perm(x1[d], x0[d], 0x05040100u);
+        xp[2 * d + 1] = __builtin_amdgcn_perm(x1[d], x0[d], 0x07060302u);
+      }
+#pragma unroll
+      for (int o = 0; o < DW_TW; ++o)
+#pragma unroll
+        for (int t = 0; t < WP; ++t)
+          if (c == o * STRIDE + 2 * t) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              acc[o][e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xp[e]),
+                                                          __builtin_bit_cast(bf16x2_t, wp[t][e]), acc[o][e], false);
+          }
     }
   }
   float sc[8], sh[8];
