@@ -235,6 +235,12 @@ void sna_supernet_free(sna_supernet* net);
  * for timing and for checking that property.  Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
 sna_status sna_set_k_split(sna_supernet* net, int32_t mode);
 
+/* Test / timing knob: force every conv / linear launch of the matrix kernel onto tile variant
+ * `variant` (0 <= variant < sna_tile_variant_count()), or back to the measured / heuristic choice
+ * with -1.  The result does not depend on the variant.  Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
+int32_t sna_tile_variant_count(void);
+sna_status sna_set_tile_variant(sna_supernet* net, int32_t variant);
+
 /* Multiply-accumulate count and launch count of the last successful forward on
  * this handle (host bookkeeping for reports). */
 sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t* launches);

@@ -90,6 +90,8 @@ def lib():
     L.sna_last_forward_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32)]; L.sna_last_forward_info.restype = i32
     L.sna_profile_enable.argtypes = [vp, i32]; L.sna_profile_enable.restype = i32
     L.sna_set_k_split.argtypes = [vp, i32]; L.sna_set_k_split.restype = i32
+    L.sna_set_tile_variant.argtypes = [vp, i32]; L.sna_set_tile_variant.restype = i32
+    L.sna_tile_variant_count.argtypes = []; L.sna_tile_variant_count.restype = i32
     L.sna_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     L.sna_profile_read.restype = i32
@@ -302,6 +304,9 @@ class Supernet:
         m, l = C.c_int64(), C.c_int32()
         _check(lib().sna_last_forward_info(self.handle, C.byref(m), C.byref(l)))
         return m.value, l.value
+
+    def set_tile_variant(self, variant):
+        _check(lib().sna_set_tile_variant(self.handle, int(variant)))
 
     def set_k_split(self, mode):
         _check(lib().sna_set_k_split(self.handle, int(mode)))

@@ -292,6 +292,7 @@ struct Fwd {
       }
       auto it = net->tuned.find(tune_key(q, q.parts));
       if (it != net->tuned.end()) var[i] = it->second;
+      if (net->forced_variant >= 0) var[i] = net->forced_variant;
       place(q, var[i]);
     }
     if ((unify || n > 1) && !net->tuning) {
@@ -1378,6 +1379,16 @@ sna_status sna_tuning_import(sna_supernet* net, const char* text, int64_t len) {
   }
   for (const auto& kv : tv) net->tuned[kv.first] = kv.second;
   for (const auto& kv : ts) net->tuned_split[kv.first] = kv.second;
+  net->plans.clear();
+  return SNA_OK;
+}
+
+int32_t sna_tile_variant_count(void) { return igemm_num_variants(); }
+
+sna_status sna_set_tile_variant(sna_supernet* net, int32_t variant) {
+  if (!net) return fail(SNA_E_NULL, "net is NULL");
+  if (variant < -1 || variant >= igemm_num_variants()) return fail(SNA_E_CFG_RANGE, "tile variant %d", variant);
+  net->forced_variant = variant;
   net->plans.clear();
   return SNA_OK;
 }

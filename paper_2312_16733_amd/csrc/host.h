@@ -81,6 +81,7 @@ struct sna_supernet {
   std::map<std::array<int, 6>, int> tuned;
   // measured for a chunked layer shape: 1 = one block per K chunk plus the reduction kernel is faster
   std::map<std::array<int, 6>, int> tuned_split;
+  int forced_variant = -1;           // >= 0: every igemm launch uses this tile variant (test knob)
   bool tuning = false;               // the forward in progress measures shapes it has no entry for
   // launch lists of recent forward calls, replayed when the same cfgs / routing come again
   std::vector<sna::Plan> plans;

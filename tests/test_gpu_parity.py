@@ -534,3 +534,39 @@ def test_tuning_table_round_trip_and_rejects_bad_lines(torch_mod):
     finally:
         net.close()
         other.close()
+
+
+def test_every_tile_variant_gives_the_same_bits(torch_mod, resnet_full, tf_full):
+    """Each tile variant of the matrix kernel (plain and wave-specialised, every tile shape) forced onto
+    every layer: ragged rows and columns, chunked reductions, split reductions; same bits as the default."""
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    nv = sna.lib().sna_tile_variant_count()
+    assert nv >= 7
+    spec, W, S, C, net = resnet_full
+    cases = [(C[15], 2), (C[3], 5)]
+    try:
+        for c, batch in cases:
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 24)
+            ref = run_single(torch, net, spec, c, x)
+            for mode in (0, 2):
+                net.set_k_split(mode)
+                for v in range(nv):
+                    net.set_tile_variant(v)
+                    say("tile variant", v, "k split mode", mode, "batch", batch)
+                    np.testing.assert_array_equal(run_single(torch, net, spec, c, x), ref, err_msg=f"variant {v} mode {mode}")
+    finally:
+        net.set_tile_variant(-1)
+        net.set_k_split(0)
+    spec, W, S, C, net = tf_full
+    try:
+        c = C[7]
+        x = synth.make_inputs(spec, 3, c.in_h, c.in_w, 25)
+        ref = run_tf(torch, net, spec, [c], np.zeros(3, np.int32), x)
+        for v in range(nv):
+            net.set_tile_variant(v)
+            got = run_tf(torch, net, spec, [c], np.zeros(3, np.int32), x)
+            np.testing.assert_array_equal(got[0], ref[0], err_msg=f"variant {v}")
+            np.testing.assert_array_equal(got[1], ref[1], err_msg=f"variant {v} hidden")
+    finally:
+        net.set_tile_variant(-1)
