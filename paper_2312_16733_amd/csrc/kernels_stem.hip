@@ -1,5 +1,8 @@
 // ResNet stem in one kernel: 7x7 stride-2 WeightSlice conv over the channel-padded request image,
-// SubnetNorm scale/shift, ReLU and the 3x3 stride-2 max pool that follows it.
+// SubnetNorm scale/shift, ReLU and the 3x3 stride-2 max pool that follows it.  (WeightSlice and
+// SubnetNorm operators of the paper's section "SubNetAct: Instantaneous Model Actuation": the block
+// reads the leading K_active output channels of the resident 7x7 stem tensor in place and applies the
+// subnet's own folded statistics.)
 //
 // The generic implicit GEMM gathers the stem's 49 taps per output pixel through the texture path
 // (16 bytes each) and writes a full-resolution activation that the pool reads straight back; here
