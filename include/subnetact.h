@@ -197,13 +197,19 @@ sna_status sna_subnet_forward(sna_supernet* net,
                               void* hidden_dev, void* hip_stream);
 
 /* Same arguments and result as sna_subnet_forward, but every conv / linear layer
- * shape met for the first time on this handle is timed with each tile variant of
- * the matrix kernel (a few launches each, synchronising on the stream), and the
- * fastest is remembered for later sna_subnet_forward calls with that layer shape.
- * The paper's serving system profiles each subnet offline before serving; this
- * is the same step for the kernels.  Tile variants do not change a bit of the
- * result.  Returns after the stream has drained.  Not for use under stream
- * capture.  Errors: as sna_subnet_forward. */
+ * shape met for the first time on this handle gets a measured tile variant of the
+ * matrix kernel, remembered for later sna_subnet_forward calls with that shape.
+ * Two steps: each new shape alone, launched back to back with every variant (this
+ * also decides whether a long reduction is split over blocks); then, if the call
+ * met any new shape, the whole forward is run with every launch forced to one
+ * variant, for each variant in turn, every launch timed between two events, and a
+ * new shape keeps the variant with the least time inside the forward (operands
+ * come from HBM there, not from caches warmed by the previous repeat).  Step 2 is
+ * skipped while sna_profile_enable is on.  The paper's serving system profiles
+ * each subnet offline before serving; this is the same step for the kernels.
+ * Tile variants do not change a bit of the result.  Synchronises on the stream
+ * many times; returns after it has drained.  Not for use under stream capture.
+ * Errors: as sna_subnet_forward. */
 sna_status sna_subnet_tune(sna_supernet* net,
                            const sna_subnet_cfg* cfgs, int32_t n_cfgs,
                            const int32_t* req_cfg, int32_t n_requests,
@@ -255,6 +261,13 @@ sna_status sna_profile_enable(sna_supernet* net, int32_t on);
 sna_status sna_profile_read(sna_supernet* net, double ms[SNA_N_KCLASS], int64_t launches[SNA_N_KCLASS],
                             double flops[SNA_N_KCLASS], double bytes[SNA_N_KCLASS]);
 const char* sna_profile_class_name(int32_t kclass);
+/* The launches recorded since the last sna_profile_read(), one text line each in
+ * launch order: microseconds between the launch's two events, class name, then
+ * for the grouped kernels the tile variant and every problem's active shape.
+ * Syncs the events; does not clear them (sna_profile_read() does).  Writes at most
+ * cap - 1 bytes plus a NUL into buf (host memory, may be NULL) and returns the
+ * full length, or -1 on error. */
+int64_t sna_profile_read_launches(sna_supernet* net, char* buf, int64_t cap);
 
 const char* sna_last_error(void);
 

@@ -96,6 +96,7 @@ def lib():
                                    C.POINTER(C.c_double)]
     L.sna_profile_read.restype = i32
     L.sna_profile_class_name.argtypes = [i32]; L.sna_profile_class_name.restype = C.c_char_p
+    L.sna_profile_read_launches.argtypes = [vp, C.c_char_p, i64]; L.sna_profile_read_launches.restype = i64
     _lib = L
     return L
 
@@ -313,6 +314,14 @@ class Supernet:
 
     def profile_enable(self, on: bool):
         _check(lib().sna_profile_enable(self.handle, int(on)))
+
+    def profile_read_launches(self) -> str:
+        n = lib().sna_profile_read_launches(self.handle, None, 0)
+        if n < 0:
+            raise SnaError(-1, lib().sna_last_error().decode())
+        buf = C.create_string_buffer(n + 1)
+        lib().sna_profile_read_launches(self.handle, buf, n + 1)
+        return buf.value.decode()
 
     def profile_read(self):
         ms = (C.c_double * N_KCLASS)(); la = (C.c_int64 * N_KCLASS)()

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <functional>
+#include <set>
 
 #include "host.h"
 
@@ -1051,6 +1052,51 @@ static void visit_io_pointers(const PlanOp& op, F&& f) {
 }
 
 // Run a launch list on the stream, with the per-launch event brackets when timing is enabled.
+// Tuning key (M, K_out, C_in, taps, stride, parts) of the problem with the most work in a matrix-kernel
+// launch: the one whose tile variant the whole launch uses.
+static std::array<int, 6> lead_key(const PlanOp& op) {
+  const ConvGroupArgs& a = *(const ConvGroupArgs*)op.args.data();
+  int lead = 0;
+  double lead_work = -1;
+  for (int i = 0; i < a.n; ++i) {
+    const ConvProblem& q = a.p[i];
+    const double work = (double)q.M * q.K * (q.C * q.R * q.S + 64.0);
+    if (work > lead_work) { lead_work = work; lead = i; }
+  }
+  const ConvProblem& q = a.p[lead];
+  return {q.M, q.K, q.C, q.R * q.S, q.stride, q.parts};
+}
+
+// One line of text for a launch: what the per-launch profile lists beside its time.
+static std::string describe_op(const PlanOp& op) {
+  char t[160];
+  std::string out;
+  if (op.type == PlanOp::IGEMM || op.type == PlanOp::KREDUCE || op.type == PlanOp::DIRECT) {
+    const ConvGroupArgs& a = *(const ConvGroupArgs*)op.args.data();
+    if (op.type == PlanOp::IGEMM) { snprintf(t, sizeof(t), "tile=%d chunked=%d", op.variant, op.flag); out = t; }
+    for (int i = 0; i < a.n; ++i) {
+      const ConvProblem& q = a.p[i];
+      snprintf(t, sizeof(t), " [M=%d K=%d C=%d %dx%d/%d parts=%d tiles=%d]", q.M, q.K, q.C, q.R, q.S, q.stride, q.parts, q.tiles);
+      out += t;
+    }
+  } else if (op.type == PlanOp::DW) {
+    const DwGroupArgs& a = *(const DwGroupArgs*)op.args.data();
+    for (int i = 0; i < a.n; ++i) {
+      const DwProblem& q = a.p[i];
+      snprintf(t, sizeof(t), " [N=%d H=%d C=%d %dx%d/%d]", q.N, q.H, q.C, q.k, q.k, q.stride);
+      out += t;
+    }
+  } else if (op.type == PlanOp::SE) {
+    const SeGroupArgs& a = *(const SeGroupArgs*)op.args.data();
+    snprintf(t, sizeof(t), "phase=%d", op.flag); out = t;
+    for (int i = 0; i < a.n; ++i) {
+      snprintf(t, sizeof(t), " [N=%d HW=%d C=%d Q=%d]", a.p[i].N, a.p[i].HW, a.p[i].C, a.p[i].Q);
+      out += t;
+    }
+  }
+  return out;
+}
+
 static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t stream) {
   for (const PlanOp& op : plan.ops) {
     hipEvent_t a = nullptr, b = nullptr;
@@ -1069,7 +1115,9 @@ static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t 
     const hipError_t e = run_op(op, stream);
     if (e != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(e));
     if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
-      net->prof_recs.push_back({op.kc, a, b});
+      ProfRec rec{op.kc, a, b, describe_op(op)};
+      if (op.type == PlanOp::IGEMM) { rec.igemm = true; rec.key = lead_key(op); }
+      net->prof_recs.push_back(std::move(rec));
       net->prof_flops[op.kc] += op.flops;
       net->prof_bytes[op.kc] += op.bytes;
       net->prof_launches[op.kc] += 1;
@@ -1325,12 +1373,75 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
                            int32_t n_requests, const void* inputs_dev, float* logits_dev, void* hidden_dev,
                            void* hip_stream) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
+  std::set<std::array<int, 6>> known;
+  for (const auto& kv : net->tuned) known.insert(kv.first);
+  // Step 1: every new layer shape alone, launched back to back with each variant (also decides
+  // whether a chunked reduction is split over blocks).
   net->tuning = true;
   net->plans.clear();                      // launch lists built before this call may use other tile variants
   sna_status st = sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
   net->tuning = false;
   if (st == SNA_OK && hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return fail(SNA_E_HIP, "stream synchronize");
-  return st;
+  bool any_new = false;
+  for (const auto& kv : net->tuned) any_new = any_new || !known.count(kv.first);
+  if (st != SNA_OK || !any_new || net->prof_on || n_requests == 0) return st;
+  // Step 2: a layer launched back to back finds its operands in the caches, which it does not inside
+  // a forward, and that changes which variant wins.  So the whole forward is run with every launch
+  // forced to variant v, for each v in turn (rounds interleaved against clock drift), each launch
+  // timed between two events; a new shape gets the variant with the least median time summed
+  // over the launches it leads.
+  const bool cache_was = net->plan_cache_on;
+  const int forced_was = net->forced_variant;
+  net->plan_cache_on = false;
+  net->prof_on = true;
+  const int nv = igemm_num_variants(), rounds = 3;
+  std::map<std::array<int, 6>, std::vector<std::vector<double>>> samples;   // key -> [variant][round]
+  for (int round = 0; round <= rounds && st == SNA_OK; ++round)             // round 0 warms up, not recorded
+    for (int v = 0; v < nv && st == SNA_OK; ++v) {
+      net->forced_variant = v;
+      net->prof_recs.clear();
+      net->ev_used = 0;
+      st = sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
+      if (st != SNA_OK) break;
+      std::map<std::array<int, 6>, double> sum;
+      for (const ProfRec& r : net->prof_recs) {
+        if (!r.igemm) continue;
+        float ms = 0;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+        if (e != hipSuccess) { st = fail(SNA_E_HIP, "event: %s", hipGetErrorString(e)); break; }
+        sum[r.key] += ms;
+      }
+      if (round == 0) continue;
+      for (const auto& kv : sum) {
+        auto& per_variant = samples[kv.first];
+        per_variant.resize(nv);
+        per_variant[v].push_back(kv.second);
+      }
+    }
+  net->prof_recs.clear();
+  net->ev_used = 0;
+  for (int i = 0; i < SNA_N_KCLASS; ++i) { net->prof_launches[i] = 0; net->prof_flops[i] = 0; net->prof_bytes[i] = 0; }
+  net->prof_on = false;
+  net->plan_cache_on = cache_was;
+  net->forced_variant = forced_was;
+  if (st != SNA_OK) return st;
+  for (auto& kv : samples) {
+    if (known.count(kv.first)) continue;
+    int best = -1;
+    double best_t = 0;
+    for (int v = 0; v < nv; ++v) {
+      std::vector<double>& t = kv.second[v];
+      if (t.empty()) continue;
+      std::sort(t.begin(), t.end());
+      const double med = t[t.size() / 2];
+      if (best < 0 || med < best_t) { best = v; best_t = med; }
+    }
+    if (best >= 0) net->tuned[kv.first] = best;
+  }
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return fail(SNA_E_HIP, "stream synchronize");
+  // leave the caller's outputs as a plain forward would
+  return sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
 }
 
 int32_t sna_tuned_count(const sna_supernet* net) { return net ? (int32_t)(net->tuned.size() + net->tuned_split.size()) : 0; }
@@ -1405,6 +1516,26 @@ sna_status sna_profile_enable(sna_supernet* net, int32_t on) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
   net->prof_on = on != 0;
   return SNA_OK;
+}
+
+int64_t sna_profile_read_launches(sna_supernet* net, char* buf, int64_t cap) {
+  if (!net) { fail(SNA_E_NULL, "net is NULL"); return -1; }
+  std::string out;
+  char t[96];
+  for (const ProfRec& r : net->prof_recs) {
+    hipError_t e = hipEventSynchronize(r.b);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e != hipSuccess) { fail(SNA_E_HIP, "event: %s", hipGetErrorString(e)); return -1; }
+    snprintf(t, sizeof(t), "%.3f %s ", ms * 1e3, kClassNames[r.kc]);
+    out += t; out += r.what; out += '\n';
+  }
+  if (buf && cap > 0) {
+    const size_t ncopy = std::min((size_t)cap - 1, out.size());
+    memcpy(buf, out.data(), ncopy);
+    buf[ncopy] = 0;
+  }
+  return (int64_t)out.size();
 }
 
 sna_status sna_profile_read(sna_supernet* net, double ms[SNA_N_KCLASS], int64_t launches[SNA_N_KCLASS],

@@ -28,7 +28,11 @@ struct ArchTables {
 sna_status build_tables(const sna_arch_desc* arch, ArchTables* t);
 sna_status fail(sna_status st, const char* fmt, ...);
 
-struct ProfRec { int kc; hipEvent_t a, b; };
+struct ProfRec {
+  int kc; hipEvent_t a, b; std::string what;
+  bool igemm = false;                // a matrix-kernel launch: `key` is the tuning key of its problem with the most work
+  std::array<int, 6> key{};
+};
 
 struct Group {
   const sna_subnet_cfg* cfg = nullptr;

@@ -570,3 +570,31 @@ def test_every_tile_variant_gives_the_same_bits(torch_mod, resnet_full, tf_full)
             np.testing.assert_array_equal(got[1], ref[1], err_msg=f"variant {v} hidden")
     finally:
         net.set_tile_variant(-1)
+
+
+def test_per_launch_profile_lists_every_launch(torch_mod, resnet_full):
+    """sna_profile_read_launches: one line per launch of the forward, in order, each with a time, a class
+    name and (matrix kernel) the active shapes; the class totals of sna_profile_read cover the same launches."""
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    c = C[3]
+    x = synth.make_inputs(spec, 3, c.in_h, c.in_w, 31)
+    ref = run_single(torch, net, spec, c, x)
+    net.profile_enable(True)
+    try:
+        got = run_single(torch, net, spec, c, x)
+        lines = net.profile_read_launches().strip().split("\n")
+        classes = net.profile_read()
+    finally:
+        net.profile_enable(False)
+    np.testing.assert_array_equal(ref, got)
+    assert len(lines) == net.last_forward_info()[1] == sum(v["launches"] for v in classes.values())
+    total = 0.0
+    for line in lines:
+        us, cls = line.split(" ")[:2]
+        assert float(us) > 0 and cls in classes
+        total += float(us)
+    assert abs(total * 1e-3 - sum(v["ms"] for v in classes.values())) < 1e-3 * len(lines)
+    first_conv = next(l for l in lines if "igemm_conv_linear" in l)
+    assert "tile=" in first_conv and f"C={c.stage_out_ch[0]} " in first_conv
+    assert net.profile_read_launches() == ""
