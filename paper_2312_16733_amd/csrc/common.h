@@ -68,16 +68,10 @@ struct ConvGroupArgs {
   ConvProblem p[SNA_MAX_GROUPS];
 };
 
-// Global average pool ahead of a squeeze-excite gate: the pixels of a request are cut into up to
-// SNA_GAP_MAX_SEGS segments (a function of H*W only) summed by different blocks; the gate adds the
-// segment sums in order.
-#define SNA_GAP_MAX_SEGS 8
-
 struct PoolProblem {    // max pool 3x3/2 or global average pool
   const void* x; void* y;
   int N, H, W, C, Ho, Wo;
   int out_fp32;         // global average pool only: write fp32 instead of the storage dtype
-  int segs;             // global average pool only: > 1 = write fp32 segment sums [segs][N][C], not the mean
   int tile_start, tiles;
 };
 struct PoolGroupArgs { int n; PoolProblem p[SNA_MAX_GROUPS]; };
@@ -88,6 +82,10 @@ struct DwProblem {
   int k, stride, pad;
   int wr, ws;           // element strides of the stored [R][S][C_max] kernel
   int act;
+  // Squeeze-excite pool fused into the layer: the grid is laid out per request (bpr blocks each) and
+  // every block writes the sums of its own outputs, as stored, per channel: pool_part[n][block][C].
+  float* pool_part;     // nullptr: flat grid, no pool
+  int bpr;
   int tile_start, tiles;
 };
 struct DwGroupArgs { int n; DwProblem p[SNA_MAX_GROUPS]; };
@@ -97,12 +95,11 @@ struct SeProblem {
   void* y;              // gated output (may alias x)
   const void* w1; const float* b1;  // [Q_max][C_max] stored; leading [Q][C] used
   const void* w2; const float* b2;  // [C_max][Q_max]
-  float* pooled;        // [pool_segs][N][C] segment sums of the pool (the mean when pool_segs == 1)
-  float* gate;          // [N][C] scratch
+  float* pooled;        // [N][pool_segs][C] partial sums of the pool, written by the depthwise kernel's blocks
   float* hidden;        // [N][Q] scratch
   int N, HW, C, Q;
   int w1_stride, w2_stride;
-  int pool_segs;        // > 1: pooled holds sums, scaled by inv_hw here
+  int pool_segs;        // partial sums per request, added in order and scaled by inv_hw
   float inv_hw;
   int tile_start, tiles;
 };
@@ -161,6 +158,7 @@ hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(const PoolGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_gap(const PoolGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s);
+int depthwise_pool_blocks(int Ho, int Wo, int C);   // blocks per request of a depthwise layer with the fused pool
 hipError_t launch_se(const SeGroupArgs& a, hipStream_t s);
 hipError_t launch_layernorm(const LnGroupArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnGroupArgs& a, hipStream_t s);

@@ -416,11 +416,6 @@ struct Fwd {
     run_igemm(ps, true);
   }
 
-  // segments of the squeeze-excite pool: by image size only, so that a request's sum order is fixed
-  static int gap_segs(int hw) {
-    const int s = hw / 64;
-    return s < 1 ? 1 : (s > SNA_GAP_MAX_SEGS ? SNA_GAP_MAX_SEGS : s);
-  }
 
   void pool_slot(bool is_max, const std::function<bool(Group&, PoolProblem&)>& fill) {
     PoolGroupArgs a;
@@ -437,7 +432,7 @@ struct Fwd {
         p.tiles = (int)((total + 255) / 256);
       } else {
         p.Ho = p.Wo = 1;
-        p.tiles = p.N * ((p.C / 8 + 31) / 32) * (p.segs > 1 ? p.segs : 1);
+        p.tiles = p.N * ((p.C / 8 + 31) / 32);
       }
       p.tile_start = start;
       start += p.tiles;
@@ -789,16 +784,13 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
         slice_dw(p, tensor(pre + "dw.w"), g.cfg->block_kernel[s][j], st);
         p.scale = scale_of(pre + "sn2", g.cfg->subnet_id); p.shift = shift_of(pre + "sn2", g.cfg->subnet_id);
         p.act = act; p.y = g.buf[3];
+        if (a.stage_se[s]) {                                    // the gate's average pool rides on this launch
+          p.pool_part = g.small;
+          p.bpr = depthwise_pool_blocks(p.Ho, p.Wo, p.C);
+        }
         return true;
       });
       if (a.stage_se[s]) {
-        pool_slot(false, [&](Group& g, PoolProblem& p) {
-          if (!on(g)) return false;
-          p.x = g.buf[3]; p.N = g.n; p.H = out_size(g.H, 3, st); p.W = out_size(g.W, 3, st);
-          p.C = g.cfg->block_mid_ch[s][j]; p.y = g.small; p.out_fp32 = 1;
-          p.segs = gap_segs(p.H * p.W);
-          return true;
-        });
         se_slot([&](Group& g, SeProblem& p) {
           if (!on(g)) return false;
           const int m = g.cfg->block_mid_ch[s][j];
@@ -807,10 +799,11 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
           p.x = g.buf[3]; p.y = g.buf[3];
           p.w1 = wptr(t1); p.b1 = (const float*)wptr(tensor(pre + "se.fc1.b")); p.w1_stride = t1.dims[1];
           p.w2 = wptr(t2); p.b2 = (const float*)wptr(tensor(pre + "se.fc2.b")); p.w2_stride = t2.dims[1];
-          p.N = g.n; p.HW = out_size(g.H, 3, st) * out_size(g.W, 3, st); p.C = m; p.Q = g.cfg->block_aux_ch[s][j];
-          p.pool_segs = gap_segs(p.HW); p.inv_hw = 1.f / (float)p.HW;
-          p.pooled = g.small; p.gate = g.small + (size_t)p.pool_segs * g.n * m;
-          p.hidden = p.gate + (size_t)g.n * m;
+          const int ho = out_size(g.H, 3, st), wo = out_size(g.W, 3, st);
+          p.N = g.n; p.HW = ho * wo; p.C = m; p.Q = g.cfg->block_aux_ch[s][j];
+          p.pool_segs = depthwise_pool_blocks(ho, wo, m); p.inv_hw = 1.f / (float)p.HW;
+          p.pooled = g.small;                                  // written by the depthwise launch above
+          p.hidden = g.small + (size_t)p.pool_segs * g.n * m;
           return true;
         });
       }

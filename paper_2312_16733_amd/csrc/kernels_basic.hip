@@ -185,23 +185,18 @@ __global__ __launch_bounds__(256) void gap_kernel(const PoolGroupArgs args) {
   const PoolProblem& p = args.p[g];
   const int cvn = p.C / VEC;
   const int cblocks = (cvn + 31) / 32;
-  const int segs = p.segs > 1 ? p.segs : 1;
-  int local = blockIdx.x - p.tile_start;
-  const int seg = local % segs;
-  local /= segs;
+  const int local = blockIdx.x - p.tile_start;
   const int n = local / cblocks;
   const int cv = (local % cblocks) * 32 + (threadIdx.x & 31);
   const int hl = threadIdx.x >> 5;
   const int HW = p.H * p.W;
-  const int seg_len = (HW + segs - 1) / segs;
-  const int h_begin = seg * seg_len, h_end = h_begin + seg_len < HW ? h_begin + seg_len : HW;
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   if (cv < cvn) {
     const T* x = (const T*)p.x + (long)n * HW * p.C + cv * VEC;
 #pragma unroll 4
-    for (int h = h_begin + hl; h < h_end; h += 8) {
+    for (int h = hl; h < HW; h += 8) {
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[i] += ld_f32<T>(x + (long)h * p.C + i);
     }
@@ -210,14 +205,14 @@ __global__ __launch_bounds__(256) void gap_kernel(const PoolGroupArgs args) {
   for (int i = 0; i < VEC; ++i) red[hl][threadIdx.x & 31][i] = acc[i];
   __syncthreads();
   if (hl == 0 && cv < cvn) {
-    const float inv = segs > 1 ? 1.f : 1.f / (float)HW;        // segment sums are scaled by their reader
-    const long yo = ((long)seg * p.N + n) * p.C + cv * VEC;
+    const float inv = 1.f / (float)HW;
+    const long yo = (long)n * p.C + cv * VEC;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += red[j][threadIdx.x & 31][i];
-      if (p.out_fp32 || segs > 1) ((float*)p.y)[yo + i] = sum * inv;
+      if (p.out_fp32) ((float*)p.y)[yo + i] = sum * inv;
       else st_f32<T>((T*)p.y + yo + i, sum * inv);
     }
   }

@@ -27,18 +27,37 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 // thread loads the (TW-1)*STRIDE + K input columns it needs once and reuses them across its TW
 // outputs, so an input element is fetched K (not K*K) times per output row from L1/L2 and once
 // from HBM.  y = act(scale[c] * sum_{r,s} x * w[r0+r][s0+s][c] + shift[c]).
+//
+// POOL (the layer feeds a squeeze-excite gate): blocks are laid out per request, and each block
+// also leaves the per-channel sum of the outputs it stored (the rounded values, which is what the
+// gate's average pool is defined on), added in a fixed order: per thread over its outputs, then over
+// the block's threads of one channel group in thread order.  The gate adds the blocks' sums in order.
 // ---------------------------------------------------------------------------------------------
 constexpr int DW_TW = 4;
 
-template <int K, int STRIDE>
+template <int K, int STRIDE, bool POOL>
 __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) {
   const int g = find_problem(args, blockIdx.x);
   const DwProblem& p = args.p[g];
   const int c8n = p.C >> 3;
   const int strips = (p.Wo + DW_TW - 1) / DW_TW;
-  const long idx = (long)(blockIdx.x - p.tile_start) * 256 + threadIdx.x;
-  const long total = (long)p.N * p.Ho * strips * c8n;
-  if (idx >= total) return;
+  const long per_req = (long)p.Ho * strips * c8n;
+  const int block = blockIdx.x - p.tile_start;
+  long idx;
+  bool valid;
+  if (POOL) {
+    const long in_req = (long)(block % p.bpr) * 256 + threadIdx.x;
+    valid = in_req < per_req;
+    idx = (long)(block / p.bpr) * per_req + in_req;
+  } else {
+    idx = (long)block * 256 + threadIdx.x;
+    valid = idx < per_req * p.N;
+    if (!valid) return;
+  }
+  float psum[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) psum[e] = 0.f;
+  if (valid) {
   const int c8 = idx % c8n;
   long t = idx / c8n;
   const int qs = t % strips; t /= strips;
@@ -124,40 +143,85 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) 
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = apply_act(fmaf(acc[o][e], sc[e], sh[e]), p.act);
-    *(uint4*)(y + (long)(q0 + o) * p.C) = pack8(v);
+    const uint4 packed = pack8(v);
+    *(uint4*)(y + (long)(q0 + o) * p.C) = packed;
+    if (POOL) {
+      unpack8(packed, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) psum[e] += v[e];
+    }
+  }
+  }
+  if (POOL) {
+    __shared__ float red[8][256];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[e][threadIdx.x] = psum[e];
+    __syncthreads();
+    // thread t < c8n owns the channel group of the block's t-th element; its other elements sit c8n apart
+    if ((int)threadIdx.x < c8n) {
+      const int in_block = block % p.bpr;
+      const int c8 = (int)(((long)in_block * 256 + threadIdx.x) % c8n);
+      float s8[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s8[e] = 0.f;
+      for (int t = threadIdx.x; t < 256; t += c8n)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s8[e] += red[e][t];
+      float* out = p.pool_part + ((long)block * p.C) + c8 * 8;     // block = n * bpr + in_block
+      *(float4*)out = make_float4(s8[0], s8[1], s8[2], s8[3]);
+      *(float4*)(out + 4) = make_float4(s8[4], s8[5], s8[6], s8[7]);
+    }
   }
 }
 
 hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s) {
-  // one launch per (kernel size, stride) present among the problems
-  for (int k = 3; k <= 7; k += 2)
-    for (int st = 1; st <= 2; ++st) {
-      DwGroupArgs b;
-      b.n = 0;
-      int start = 0;
-      for (int i = 0; i < a.n; ++i) {
-        if (a.p[i].k != k || a.p[i].stride != st) continue;
-        DwProblem p = a.p[i];
-        const long strips = (p.Wo + DW_TW - 1) / DW_TW;
-        p.tiles = (int)(((long)p.N * p.Ho * strips * (p.C / 8) + 255) / 256);
-        p.tile_start = start;
-        start += p.tiles;
-        b.p[b.n++] = p;
-      }
-      if (!b.n) continue;
-#define SNA_DW(KK, SS) if (k == KK && st == SS) hipLaunchKernelGGL((depthwise_kernel<KK, SS>), dim3(start), dim3(256), 0, s, b)
-      SNA_DW(3, 1); SNA_DW(3, 2); SNA_DW(5, 1); SNA_DW(5, 2); SNA_DW(7, 1); SNA_DW(7, 2);
+  // one launch per (kernel size, stride, with / without pool) present among the problems
+  for (int pool = 0; pool < 2; ++pool)
+    for (int k = 3; k <= 7; k += 2)
+      for (int st = 1; st <= 2; ++st) {
+        DwGroupArgs b;
+        b.n = 0;
+        int start = 0;
+        for (int i = 0; i < a.n; ++i) {
+          if (a.p[i].k != k || a.p[i].stride != st || (a.p[i].pool_part != nullptr) != (pool == 1)) continue;
+          DwProblem p = a.p[i];
+          const long strips = (p.Wo + DW_TW - 1) / DW_TW;
+          const long per_req = (long)p.Ho * strips * (p.C / 8);
+          if (pool) {
+            // every block must meet every channel group, or some sums would never be written
+            if (p.C / 8 > 256 || p.bpr != (int)((per_req + 255) / 256)) return hipErrorInvalidValue;
+            p.tiles = p.N * p.bpr;
+          } else {
+            p.tiles = (int)((per_req * p.N + 255) / 256);
+          }
+          p.tile_start = start;
+          start += p.tiles;
+          b.p[b.n++] = p;
+        }
+        if (!b.n) continue;
+#define SNA_DW(KK, SS)                                                                                              \
+  if (k == KK && st == SS) {                                                                                        \
+    if (pool) hipLaunchKernelGGL((depthwise_kernel<KK, SS, true>), dim3(start), dim3(256), 0, s, b);               \
+    else hipLaunchKernelGGL((depthwise_kernel<KK, SS, false>), dim3(start), dim3(256), 0, s, b);                   \
+  }
+        SNA_DW(3, 1); SNA_DW(3, 2); SNA_DW(5, 1); SNA_DW(5, 2); SNA_DW(7, 1); SNA_DW(7, 2);
 #undef SNA_DW
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
-    }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
   return hipSuccess;
+}
+
+int depthwise_pool_blocks(int Ho, int Wo, int C) {
+  const long strips = (Wo + DW_TW - 1) / DW_TW;
+  return (int)(((long)Ho * strips * (C / 8) + 255) / 256);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Squeeze-excite gate:
-//   z = pooled[n][:C] (fp32 mean over pixels, computed by the pooling kernel)
-//   h = relu(W1[:Q,:C] z + b1[:Q]);  gate = hardsigmoid(W2[:C,:Q] h + b2[:C])
+//   z = mean over pixels of the depthwise output (from the depthwise blocks' partial sums)
+//   h = relu(W1[:Q,:C] z + b1[:Q]);  gate = hardsigmoid(W2[:C,:Q] h + b2[:C]);  y = x * gate
+// Two launches: h per request, then gate and scaling together.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -165,100 +229,123 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One fully-connected layer of the gate: out[n][o] = f(W[o, :I] . in[n][:I] + b[o]) for o < O.
-// A block owns one request and 32 outputs; each of its 4 waves computes 8 of them, one at a
-// time: lanes read 8 consecutive bf16 weights (16 bytes) and the matching fp32 inputs, then the
-// wave reduces in a fixed butterfly order.  HSIG selects hard-sigmoid (second layer) or ReLU.
-template <bool HSIG>
-__global__ __launch_bounds__(256) void se_fc_kernel(const SeGroupArgs args) {
+// h[n][o] = relu(W1[o, :C] . z[n] + b1[o]).  A block owns one request and 32 outputs.  It first
+// builds z in LDS (partial sums added in block order, then scaled by 1 / HW); each of its 4 waves
+// then computes 8 outputs, one at a time: lanes read 8 consecutive bf16 weights (16 bytes) and the
+// matching z, and the wave reduces in a fixed butterfly order.
+__global__ __launch_bounds__(256) void se_hidden_kernel(const SeGroupArgs args) {
+  extern __shared__ __attribute__((aligned(16))) float z[];
   const int g = find_problem(args, blockIdx.x);
   const SeProblem& p = args.p[g];
-  const int I = HSIG ? p.Q : p.C, O = HSIG ? p.C : p.Q;
-  const int oblocks = (O + 31) / 32;
+  const int oblocks = (p.Q + 31) / 32;
   const int local = blockIdx.x - p.tile_start;
   const int n = local / oblocks, ob = local % oblocks;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bf16_t* w = (const bf16_t*)(HSIG ? p.w2 : p.w1);
-  const int ws = HSIG ? p.w2_stride : p.w1_stride;
-  const float* bias = HSIG ? p.b2 : p.b1;
-  const float* in = (HSIG ? p.hidden : p.pooled) + (long)n * I;
-  float* out = (HSIG ? p.gate : p.hidden) + (long)n * O;
+  const float* part = p.pooled + (long)n * p.pool_segs * p.C;
+  for (int c4 = threadIdx.x; c4 < (p.C >> 2); c4 += 256) {
+    float4 a = *(const float4*)(part + c4 * 4);
+    for (int sgm = 1; sgm < p.pool_segs; ++sgm) {
+      const float4 b = *(const float4*)(part + (long)sgm * p.C + c4 * 4);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    a.x *= p.inv_hw; a.y *= p.inv_hw; a.z *= p.inv_hw; a.w *= p.inv_hw;
+    *(float4*)(z + c4 * 4) = a;
+  }
+  __syncthreads();
+  const bf16_t* w = (const bf16_t*)p.w1;
 #pragma unroll 1
   for (int t = 0; t < 8; ++t) {
     const int o = ob * 32 + wave * 8 + t;
-    if (o >= O) break;
+    if (o >= p.Q) break;
     float a = 0.f;
-    for (int i8 = lane; i8 < (I >> 3); i8 += 64) {
+    for (int i8 = lane; i8 < (p.C >> 3); i8 += 64) {
       float wv[8];
-      unpack8(*(const uint4*)(w + (long)o * ws + i8 * 8), wv);
-      float4 x0 = *(const float4*)(in + i8 * 8), x1 = *(const float4*)(in + i8 * 8 + 4);
-      if (!HSIG && p.pool_segs > 1) {           // the pool left segment sums: add them in order, then scale
-        for (int sgm = 1; sgm < p.pool_segs; ++sgm) {
-          const float* ins = in + (long)sgm * p.N * I;
-          const float4 y0 = *(const float4*)(ins + i8 * 8), y1 = *(const float4*)(ins + i8 * 8 + 4);
-          x0.x += y0.x; x0.y += y0.y; x0.z += y0.z; x0.w += y0.w;
-          x1.x += y1.x; x1.y += y1.y; x1.z += y1.z; x1.w += y1.w;
-        }
-        x0.x *= p.inv_hw; x0.y *= p.inv_hw; x0.z *= p.inv_hw; x0.w *= p.inv_hw;
-        x1.x *= p.inv_hw; x1.y *= p.inv_hw; x1.z *= p.inv_hw; x1.w *= p.inv_hw;
-      }
+      unpack8(*(const uint4*)(w + (long)o * p.w1_stride + i8 * 8), wv);
+      const float4 x0 = *(const float4*)(z + i8 * 8), x1 = *(const float4*)(z + i8 * 8 + 4);
       a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
       a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
     }
     a = wave_sum(a);
-    if (lane == 0) {
-      a += bias[o];
-      out[o] = HSIG ? fminf(fmaxf(a + 3.f, 0.f), 6.f) * (1.f / 6.f) : fmaxf(a, 0.f);
-    }
+    if (lane == 0) p.hidden[(long)n * p.Q + o] = fmaxf(a + p.b1[o], 0.f);
   }
 }
 
-// y[n, hw, c] = bf16(x[n, hw, c] * gate[n, c])
-__global__ __launch_bounds__(256) void se_scale_kernel(const SeGroupArgs args) {
+// gate[n][c] = hardsigmoid(W2[c, :Q] . h[n] + b2[c]);  y[n, hw, c] = bf16(x[n, hw, c] * gate[n][c]).
+// A block owns one request, 64 channels and SE_PIX pixels: its threads first compute the 64 gate
+// values (4 threads per channel, each a quarter of Q in order, the quarters added in order), then
+// stream the pixels, 8 lanes per pixel row of 128 bytes.  The gate is recomputed by every pixel
+// segment of a request: 64 x Q multiply-adds against one more launch and a round trip through memory.
+constexpr int SE_PIX = 256;
+__global__ __launch_bounds__(256) void se_gate_scale_kernel(const SeGroupArgs args) {
+  __shared__ float gate_s[64];
   const int g = find_problem(args, blockIdx.x);
   const SeProblem& p = args.p[g];
-  const int c8n = p.C >> 3;
-  const long idx = (long)(blockIdx.x - p.tile_start) * 256 + threadIdx.x;
-  const long total = (long)p.N * p.HW * c8n;
-  if (idx >= total) return;
-  const int c8 = idx % c8n;
-  const long pix = idx / c8n;
-  const int n = pix / p.HW;
-  float v[8];
-  unpack8(*(const uint4*)((const bf16_t*)p.x + pix * p.C + c8 * 8), v);
-  const float* gt = p.gate + (long)n * p.C + c8 * 8;
+  const int cgroups = (p.C + 63) / 64, psegs = (p.HW + SE_PIX - 1) / SE_PIX;
+  int local = blockIdx.x - p.tile_start;
+  const int pseg = local % psegs; local /= psegs;
+  const int cg = local % cgroups;
+  const int n = local / cgroups;
+  {
+    const int c = cg * 64 + (threadIdx.x >> 2), quarter = threadIdx.x & 3;
+    const int q8n = p.Q >> 3, per = (q8n + 3) >> 2;
+    float a = 0.f;
+    if (c < p.C) {
+      const bf16_t* w = (const bf16_t*)p.w2 + (long)c * p.w2_stride;
+      const float* h = p.hidden + (long)n * p.Q;
+      const int end = (quarter + 1) * per < q8n ? (quarter + 1) * per : q8n;
+      for (int i8 = quarter * per; i8 < end; ++i8) {
+        float wv[8];
+        unpack8(*(const uint4*)(w + i8 * 8), wv);
+        const float4 x0 = *(const float4*)(h + i8 * 8), x1 = *(const float4*)(h + i8 * 8 + 4);
+        a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
+        a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
+      }
+    }
+    // quarters 0..3 of a channel sit in adjacent lanes: ((q0 + q1) + (q2 + q3))
+    a += __shfl_xor(a, 1, 64);
+    a += __shfl_xor(a, 2, 64);
+    if (quarter == 0 && c < p.C) gate_s[threadIdx.x >> 2] = fminf(fmaxf(a + p.b2[c] + 3.f, 0.f), 6.f) * (1.f / 6.f);
+  }
+  __syncthreads();
+  const int c8 = cg * 8 + (threadIdx.x & 7);
+  if (c8 * 8 >= p.C) return;
+  float gt[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] *= gt[e];
-  *(uint4*)((bf16_t*)p.y + pix * p.C + c8 * 8) = pack8(v);
+  for (int e = 0; e < 8; ++e) gt[e] = gate_s[(threadIdx.x & 7) * 8 + e];
+  const int h_end = (pseg + 1) * SE_PIX < p.HW ? (pseg + 1) * SE_PIX : p.HW;
+  const bf16_t* x = (const bf16_t*)p.x + (long)n * p.HW * p.C + c8 * 8;
+  bf16_t* y = (bf16_t*)p.y + (long)n * p.HW * p.C + c8 * 8;
+#pragma unroll 4
+  for (int h = pseg * SE_PIX + (threadIdx.x >> 3); h < h_end; h += 32) {
+    float v[8];
+    unpack8(*(const uint4*)(x + (long)h * p.C), v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= gt[e];
+    *(uint4*)(y + (long)h * p.C) = pack8(v);
+  }
 }
 
 hipError_t launch_se(const SeGroupArgs& a, hipStream_t s) {
   if (a.n == 0) return hipSuccess;
   SeGroupArgs b = a;
-  int start = 0;
+  int start = 0, c_max = 0;
   for (int i = 0; i < b.n; ++i) {
-    if (b.p[i].C % 8 || b.p[i].Q % 8 || b.p[i].w1_stride % 8 || b.p[i].w2_stride % 8) return hipErrorInvalidValue;
+    if (b.p[i].C % 8 || b.p[i].Q % 8 || b.p[i].w1_stride % 8 || b.p[i].w2_stride % 8 || b.p[i].pool_segs < 1)
+      return hipErrorInvalidValue;
     b.p[i].tiles = b.p[i].N * ((b.p[i].Q + 31) / 32);
     b.p[i].tile_start = start; start += b.p[i].tiles;
+    if (b.p[i].C > c_max) c_max = b.p[i].C;
   }
-  hipLaunchKernelGGL(se_fc_kernel<false>, dim3(start), dim3(256), 0, s, b);
+  if (c_max * 4 > 64 * 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(se_hidden_kernel, dim3(start), dim3(256), c_max * 4, s, b);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   start = 0;
   for (int i = 0; i < b.n; ++i) {
-    b.p[i].tiles = b.p[i].N * ((b.p[i].C + 31) / 32);
+    b.p[i].tiles = b.p[i].N * ((b.p[i].C + 63) / 64) * ((b.p[i].HW + SE_PIX - 1) / SE_PIX);
     b.p[i].tile_start = start; start += b.p[i].tiles;
   }
-  hipLaunchKernelGGL(se_fc_kernel<true>, dim3(start), dim3(256), 0, s, b);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  start = 0;
-  for (int i = 0; i < b.n; ++i) {
-    const long total = (long)b.p[i].N * b.p[i].HW * (b.p[i].C / 8);
-    b.p[i].tiles = (int)((total + 255) / 256);
-    b.p[i].tile_start = start; start += b.p[i].tiles;
-  }
-  hipLaunchKernelGGL(se_scale_kernel, dim3(start), dim3(256), 0, s, b);
+  hipLaunchKernelGGL(se_gate_scale_kernel, dim3(start), dim3(256), 0, s, b);
   return hipGetLastError();
 }
 

@@ -162,7 +162,11 @@ sna_status build_tables(const sna_arch_desc* a, ArchTables* t) {
         b.conv(p + "project.w", c, 1, m); b.norm(p + "sn3", c);
         upd((int64_t)(j == 0 ? h : ho) * (j == 0 ? h : ho) * m);
         upd((int64_t)ho * ho * (m > c ? m : c));
-        if ((SNA_GAP_MAX_SEGS + 1) * m + q > small) small = (SNA_GAP_MAX_SEGS + 1) * m + q;   // pooled partials, gate, hidden
+        if (a->stage_se[s]) {                        // pool partial sums of the depthwise blocks, then the gate's hidden layer
+          if (m / 8 > 256) return fail(SNA_E_ARCH, "block_max_mid[%d][%d]=%d: squeeze-excite layers take at most 2048 channels", s, j, m);
+          const int64_t need = (int64_t)depthwise_pool_blocks(ho, ho, m) * m + q;
+          if (need > small) small = need;
+        }
       }
       h = ho; prev = c;
     }
