@@ -6,6 +6,7 @@ namespace sna {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int AT_S = 128;          // max tokens per request
 constexpr int AT_D = 64;           // head dim
@@ -13,12 +14,18 @@ constexpr int AT_LD = AT_S + 8;    // LDS row stride (bf16) for V^T and P
 
 // One block = one (request, head); wave w owns queries [32w, 32w + 32).
 //   scores = Q K^T / 8 (fp32) -> softmax over keys (fp32) -> P rounded to bf16 -> ctx = P V -> bf16.
+// The scores are computed transposed (K as the row operand, Q as the column operand), so that a lane
+// of the accumulator holds one query (column lane % 32) and 16 of the 32 keys of each key block:
+// the softmax reduction over keys runs inside a lane plus one exchange with lane ^ 32, and the
+// probabilities are already laid out as the row operand of the second product (row = query, 8
+// values per K slice) without a trip through LDS.  The slice's 8 values are keys
+// {base + 4 hi + 0..3, base + 8 + 4 hi + 0..3} (hi = lane / 32) instead of 8 consecutive keys; a
+// sum over keys may take them in any order as long as the V operand uses the same one, and V^T in
+// LDS gives each lane its two runs of 4 keys as two 8-byte reads.
 // Q and K fragments come straight from global memory (a lane's 8 consecutive head-dim values are
-// contiguous); V is transposed through LDS and P goes through LDS to turn the accumulator layout
-// (lane = key) into the operand layout (lane = query).
+// contiguous); V is transposed through LDS.
 __global__ __launch_bounds__(256) void attention_kernel(const AttnGroupArgs args) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[AT_D * AT_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t Ps[4 * 32 * AT_LD];
   const int g = find_problem(args, blockIdx.x);
   const AttnProblem& p = args.p[g];
   const int local = blockIdx.x - p.tile_start;
@@ -51,6 +58,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const AttnGroupArgs args
     if (qrow < S) v = *(const uint4*)(Q + (long)qrow * ld + ks * 16 + hi * 8);
     qf[ks] = __builtin_bit_cast(bf16x8, v);
   }
+  // sc[j][v]: query qrow, key 32 j + 8 (v / 4) + 4 hi + v % 4
   f32x16 sc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -61,49 +69,57 @@ __global__ __launch_bounds__(256) void attention_kernel(const AttnGroupArgs args
     for (int ks = 0; ks < 4; ++ks) {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (key < S) v = *(const uint4*)(Kp + (long)key * ld + ks * 16 + hi * 8);
-      sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], __builtin_bit_cast(bf16x8, v), sc[j], 0, 0, 0);
+      sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), qf[ks], sc[j], 0, 0, 0);
     }
   }
-  // softmax over keys: element v of lane l is query 8*(v/4) + 4*(l/32) + v%4, key 32j + l%32
-  bf16_t* Pw = Ps + wave * 32 * AT_LD;
+  // softmax over the keys of this lane's query, in base 2: exp(x / 8 - max) = exp2((x - max') * log2(e) / 8)
+  const float kScale = 0.125f * 1.44269504088896340736f;
+  float m = -3.0e38f;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    float s[4], m = -3.0e38f;
+  for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      s[j] = (j * 32 + r32 < S) ? sc[j][v] * 0.125f : -3.0e38f;
-      m = fmaxf(m, s[j]);
+    for (int v = 0; v < 16; ++v) {
+      const int key = 32 * j + 8 * (v >> 2) + 4 * hi + (v & 3);
+      sc[j][v] = key < S ? sc[j][v] * kScale : -3.0e38f;
+      m = fmaxf(m, sc[j][v]);
     }
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  float sum = 0.f;
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-    float sum = 0.f;
+  for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      s[j] = (j * 32 + r32 < S) ? expf(s[j] - m) : 0.f;
-      sum += s[j];
+    for (int v = 0; v < 16; ++v) {
+      const int key = 32 * j + 8 * (v >> 2) + 4 * hi + (v & 3);
+      sc[j][v] = key < S ? __builtin_amdgcn_exp2f(sc[j][v] - m) : 0.f;
+      sum += sc[j][v];
     }
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    const float inv = 1.f / sum;
-    const int row = 8 * (v >> 2) + 4 * hi + (v & 3);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) Pw[row * AT_LD + j * 32 + r32] = f32_to_bf16(s[j] * inv);
-  }
-  __syncthreads();                     // V^T complete (all waves), P of this wave written
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.f / sum;
+  __syncthreads();                     // V^T complete (all waves)
   f32x16 oc[2];
 #pragma unroll
   for (int jd = 0; jd < 2; ++jd)
 #pragma unroll
     for (int v = 0; v < 16; ++v) oc[jd][v] = 0.f;
 #pragma unroll
-  for (int ks = 0; ks < AT_S / 16; ++ks) {
-    const bf16x8 pf = *(const bf16x8*)(Pw + r32 * AT_LD + ks * 16 + hi * 8);
+  for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int jd = 0; jd < 2; ++jd) {
-      const bf16x8 vf = *(const bf16x8*)(Vt + (jd * 32 + r32) * AT_LD + ks * 16 + hi * 8);
-      oc[jd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, vf, oc[jd], 0, 0, 0);
+    for (int ap = 0; ap < 2; ++ap) {
+      // probabilities rounded to bf16: elements 8 ap .. 8 ap + 7 of the key block
+      u32x4 pw;
+      pw.x = pack_bf16x2(sc[j][8 * ap + 0] * inv, sc[j][8 * ap + 1] * inv);
+      pw.y = pack_bf16x2(sc[j][8 * ap + 2] * inv, sc[j][8 * ap + 3] * inv);
+      pw.z = pack_bf16x2(sc[j][8 * ap + 4] * inv, sc[j][8 * ap + 5] * inv);
+      pw.w = pack_bf16x2(sc[j][8 * ap + 6] * inv, sc[j][8 * ap + 7] * inv);
+      const int key0 = 32 * j + 16 * ap + 4 * hi;
+#pragma unroll
+      for (int jd = 0; jd < 2; ++jd) {
+        const bf16_t* vrow = Vt + (jd * 32 + r32) * AT_LD + key0;
+        const uint2 v0 = *(const uint2*)vrow, v1 = *(const uint2*)(vrow + 8);
+        const u32x4 vw = {v0.x, v0.y, v1.x, v1.y};
+        oc[jd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pw), __builtin_bit_cast(bf16x8, vw), oc[jd], 0, 0, 0);
+      }
     }
-  }
   bf16_t* O = (bf16_t*)p.o + (long)b * S * ld + h * AT_D;
 #pragma unroll
   for (int jd = 0; jd < 2; ++jd)
