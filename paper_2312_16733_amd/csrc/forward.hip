@@ -207,9 +207,6 @@ struct Fwd {
         ms /= reps;
         if (trial == 0 || ms < v_ms) v_ms = ms;
       }
-      if (getenv("SNA_TUNE_LOG"))
-        fprintf(stderr, "[tune] M=%d K=%d C=%d RS=%d stride=%d parts=%d chunked=%d variant %d: %.1f us\n", q.M, q.K, q.C,
-                q.R * q.S, q.stride, q.parts, (int)chunked, v, v_ms * 1e3);
       if (err == hipSuccess && (best < 0 || v_ms < *best_ms)) { best = v; *best_ms = v_ms; }
     }
     (void)hipEventDestroy(e0);

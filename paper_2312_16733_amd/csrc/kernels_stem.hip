@@ -28,7 +28,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) char lds_char;
 
 namespace stem {
-constexpr int KS = 7, TAPS = KS * KS, SLOTS = 50, NSLICE = SLOTS / 2;
+constexpr int KS = 7, SLOTS = 50;
+[[maybe_unused]] constexpr int TAPS = KS * KS, NSLICE = SLOTS / 2;     // device code only
 constexpr int PH = 4, PW = 16;
 constexpr int SH = 2 * PH + 1, SW = 2 * PW + 1, NSP = SH * SW;          // conv pixels per tile: 9 x 33 = 297
 constexpr int IH = 2 * SH + 5, IW = 2 * SW + 5, NIP = IH * IW;          // input pixels per tile: 23 x 71 = 1633
