@@ -87,7 +87,7 @@ typedef struct {
   int32_t stage_ch[SNA_MAX_STAGES];          /* max output channels of each stage */
   int32_t stage_stride[SNA_MAX_STAGES];      /* stride of block 0 of each stage */
   int32_t stage_max_depth[SNA_MAX_STAGES];
-  int32_t block_max_mid[SNA_MAX_STAGES][SNA_MAX_DEPTH]; /* max bottleneck / expanded channels */
+  int32_t block_max_mid[SNA_MAX_STAGES][SNA_MAX_DEPTH]; /* max bottleneck / expanded channels (MBV3 stages with SE: <= 2048) */
   int32_t block_max_aux[SNA_MAX_STAGES][SNA_MAX_DEPTH]; /* max squeeze channels (MBV3 SE) */
   int32_t stage_se[SNA_MAX_STAGES];          /* MBV3: 1 if the stage's blocks carry squeeze-excite */
   int32_t stage_act[SNA_MAX_STAGES];         /* MBV3: sna_act of the stage */
