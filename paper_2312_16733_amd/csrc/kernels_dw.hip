@@ -231,8 +231,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // h[n][o] = relu(W1[o, :C] . z[n] + b1[o]).  A block owns one request and 32 outputs.  It first
 // builds z in LDS (partial sums added in block order, then scaled by 1 / HW); each of its 4 waves
-// then computes 8 outputs, one at a time: lanes read 8 consecutive bf16 weights (16 bytes) and the
-// matching z, and the wave reduces in a fixed butterfly order.
+// then computes 8 outputs together: lanes read 8 consecutive bf16 weights (16 bytes) of each row and
+// the matching z, and the wave reduces each output in a fixed butterfly order.
 __global__ __launch_bounds__(256) void se_hidden_kernel(const SeGroupArgs args) {
   extern __shared__ __attribute__((aligned(16))) float z[];
   const int g = find_problem(args, blockIdx.x);
@@ -244,6 +244,7 @@ __global__ __launch_bounds__(256) void se_hidden_kernel(const SeGroupArgs args) 
   const float* part = p.pooled + (long)n * p.pool_segs * p.C;
   for (int c4 = threadIdx.x; c4 < (p.C >> 2); c4 += 256) {
     float4 a = *(const float4*)(part + c4 * 4);
+#pragma unroll 8                                    // loads in batches of 8, the additions still in block order
     for (int sgm = 1; sgm < p.pool_segs; ++sgm) {
       const float4 b = *(const float4*)(part + (long)sgm * p.C + c4 * 4);
       a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
@@ -252,21 +253,31 @@ __global__ __launch_bounds__(256) void se_hidden_kernel(const SeGroupArgs args) 
     *(float4*)(z + c4 * 4) = a;
   }
   __syncthreads();
+  // the wave's 8 rows are independent: all their weight loads are issued before the first sum is needed
+  // (one row at a time paid the L2 latency 8 times over)
   const bf16_t* w = (const bf16_t*)p.w1;
-#pragma unroll 1
-  for (int t = 0; t < 8; ++t) {
-    const int o = ob * 32 + wave * 8 + t;
-    if (o >= p.Q) break;
-    float a = 0.f;
-    for (int i8 = lane; i8 < (p.C >> 3); i8 += 64) {
+  const int o0 = ob * 32 + wave * 8;
+  float a[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) a[t] = 0.f;
+  for (int i8 = lane; i8 < (p.C >> 3); i8 += 64) {
+    const float4 x0 = *(const float4*)(z + i8 * 8), x1 = *(const float4*)(z + i8 * 8 + 4);
+    uint4 wq[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      wq[t] = o0 + t < p.Q ? *(const uint4*)(w + (long)(o0 + t) * p.w1_stride + i8 * 8) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
       float wv[8];
-      unpack8(*(const uint4*)(w + (long)o * p.w1_stride + i8 * 8), wv);
-      const float4 x0 = *(const float4*)(z + i8 * 8), x1 = *(const float4*)(z + i8 * 8 + 4);
-      a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
-      a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
+      unpack8(wq[t], wv);
+      a[t] = fmaf(wv[0], x0.x, a[t]); a[t] = fmaf(wv[1], x0.y, a[t]); a[t] = fmaf(wv[2], x0.z, a[t]); a[t] = fmaf(wv[3], x0.w, a[t]);
+      a[t] = fmaf(wv[4], x1.x, a[t]); a[t] = fmaf(wv[5], x1.y, a[t]); a[t] = fmaf(wv[6], x1.z, a[t]); a[t] = fmaf(wv[7], x1.w, a[t]);
     }
-    a = wave_sum(a);
-    if (lane == 0) p.hidden[(long)n * p.Q + o] = fmaxf(a + p.b1[o], 0.f);
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float sum = wave_sum(a[t]);
+    if (lane == 0 && o0 + t < p.Q) p.hidden[(long)n * p.Q + o0 + t] = fmaxf(sum + p.b1[o0 + t], 0.f);
   }
 }
 
@@ -276,8 +287,10 @@ __global__ __launch_bounds__(256) void se_hidden_kernel(const SeGroupArgs args) 
 // stream the pixels, 8 lanes per pixel row of 128 bytes.  The gate is recomputed by every pixel
 // segment of a request: 64 x Q multiply-adds against one more launch and a round trip through memory.
 constexpr int SE_PIX = 256;
+constexpr int SE_MAX_Q = 512;       // squeeze channels per gate (host-checked)
 __global__ __launch_bounds__(256) void se_gate_scale_kernel(const SeGroupArgs args) {
   __shared__ float gate_s[64];
+  __shared__ __attribute__((aligned(16))) float h_s[SE_MAX_Q];
   const int g = find_problem(args, blockIdx.x);
   const SeProblem& p = args.p[g];
   const int cgroups = (p.C + 63) / 64, psegs = (p.HW + SE_PIX - 1) / SE_PIX;
@@ -285,20 +298,32 @@ __global__ __launch_bounds__(256) void se_gate_scale_kernel(const SeGroupArgs ar
   const int pseg = local % psegs; local /= psegs;
   const int cg = local % cgroups;
   const int n = local / cgroups;
+  for (int i = threadIdx.x; i < p.Q; i += 256) h_s[i] = p.hidden[(long)n * p.Q + i];
+  __syncthreads();
   {
     const int c = cg * 64 + (threadIdx.x >> 2), quarter = threadIdx.x & 3;
-    const int q8n = p.Q >> 3, per = (q8n + 3) >> 2;
+    const int q8n = p.Q >> 3, per = (q8n + 3) >> 2;          // per <= SE_MAX_Q / 32
     float a = 0.f;
     if (c < p.C) {
       const bf16_t* w = (const bf16_t*)p.w2 + (long)c * p.w2_stride;
-      const float* h = p.hidden + (long)n * p.Q;
       const int end = (quarter + 1) * per < q8n ? (quarter + 1) * per : q8n;
-      for (int i8 = quarter * per; i8 < end; ++i8) {
-        float wv[8];
-        unpack8(*(const uint4*)(w + i8 * 8), wv);
-        const float4 x0 = *(const float4*)(h + i8 * 8), x1 = *(const float4*)(h + i8 * 8 + 4);
-        a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
-        a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
+      // fixed trip count, loads first: a loop over [begin, end) paid the L2 latency once per 8 weights
+      uint4 wq[SE_MAX_Q / 32];
+#pragma unroll
+      for (int j = 0; j < SE_MAX_Q / 32; ++j) {
+        const int i8 = quarter * per + j;
+        wq[j] = (j < per && i8 < end) ? *(const uint4*)(w + i8 * 8) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < SE_MAX_Q / 32; ++j) {
+        const int i8 = quarter * per + j;
+        if (j < per && i8 < end) {
+          float wv[8];
+          unpack8(wq[j], wv);
+          const float4 x0 = *(const float4*)(h_s + i8 * 8), x1 = *(const float4*)(h_s + i8 * 8 + 4);
+          a = fmaf(wv[0], x0.x, a); a = fmaf(wv[1], x0.y, a); a = fmaf(wv[2], x0.z, a); a = fmaf(wv[3], x0.w, a);
+          a = fmaf(wv[4], x1.x, a); a = fmaf(wv[5], x1.y, a); a = fmaf(wv[6], x1.z, a); a = fmaf(wv[7], x1.w, a);
+        }
       }
     }
     // quarters 0..3 of a channel sit in adjacent lanes: ((q0 + q1) + (q2 + q3))
@@ -330,7 +355,7 @@ hipError_t launch_se(const SeGroupArgs& a, hipStream_t s) {
   SeGroupArgs b = a;
   int start = 0, c_max = 0;
   for (int i = 0; i < b.n; ++i) {
-    if (b.p[i].C % 8 || b.p[i].Q % 8 || b.p[i].w1_stride % 8 || b.p[i].w2_stride % 8 || b.p[i].pool_segs < 1)
+    if (b.p[i].C % 8 || b.p[i].Q % 8 || b.p[i].Q > SE_MAX_Q || b.p[i].w1_stride % 8 || b.p[i].w2_stride % 8 || b.p[i].pool_segs < 1)
       return hipErrorInvalidValue;
     b.p[i].tiles = b.p[i].N * ((b.p[i].Q + 31) / 32);
     b.p[i].tile_start = start; start += b.p[i].tiles;
