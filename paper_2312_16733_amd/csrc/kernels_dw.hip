@@ -298,6 +298,17 @@ __global__ __launch_bounds__(256) void se_gate_scale_kernel(const SeGroupArgs ar
   const int pseg = local % psegs; local /= psegs;
   const int cg = local % cgroups;
   const int n = local / cgroups;
+  // the thread's pixels do not depend on the gate: request them first, so that their latency runs
+  // under the gate computation
+  const int c8 = cg * 8 + (threadIdx.x & 7);
+  const bool live = c8 * 8 < p.C;
+  const int h_end = (pseg + 1) * SE_PIX < p.HW ? (pseg + 1) * SE_PIX : p.HW;
+  const int h0 = pseg * SE_PIX + (threadIdx.x >> 3);
+  const bf16_t* x = (const bf16_t*)p.x + (long)n * p.HW * p.C + c8 * 8;
+  uint4 px[SE_PIX / 32];
+#pragma unroll
+  for (int j = 0; j < SE_PIX / 32; ++j)
+    px[j] = (live && h0 + 32 * j < h_end) ? *(const uint4*)(x + (long)(h0 + 32 * j) * p.C) : make_uint4(0, 0, 0, 0);
   for (int i = threadIdx.x; i < p.Q; i += 256) h_s[i] = p.hidden[(long)n * p.Q + i];
   __syncthreads();
   {
@@ -332,18 +343,17 @@ __global__ __launch_bounds__(256) void se_gate_scale_kernel(const SeGroupArgs ar
     if (quarter == 0 && c < p.C) gate_s[threadIdx.x >> 2] = fminf(fmaxf(a + p.b2[c] + 3.f, 0.f), 6.f) * (1.f / 6.f);
   }
   __syncthreads();
-  const int c8 = cg * 8 + (threadIdx.x & 7);
-  if (c8 * 8 >= p.C) return;
+  if (!live) return;
   float gt[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) gt[e] = gate_s[(threadIdx.x & 7) * 8 + e];
-  const int h_end = (pseg + 1) * SE_PIX < p.HW ? (pseg + 1) * SE_PIX : p.HW;
-  const bf16_t* x = (const bf16_t*)p.x + (long)n * p.HW * p.C + c8 * 8;
   bf16_t* y = (bf16_t*)p.y + (long)n * p.HW * p.C + c8 * 8;
-#pragma unroll 4
-  for (int h = pseg * SE_PIX + (threadIdx.x >> 3); h < h_end; h += 32) {
+#pragma unroll
+  for (int j = 0; j < SE_PIX / 32; ++j) {
+    const int h = h0 + 32 * j;
+    if (h >= h_end) break;
     float v[8];
-    unpack8(*(const uint4*)(x + (long)h * p.C), v);
+    unpack8(px[j], v);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] *= gt[e];
     *(uint4*)(y + (long)h * p.C) = pack8(v);
