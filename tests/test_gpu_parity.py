@@ -598,3 +598,28 @@ def test_per_launch_profile_lists_every_launch(torch_mod, resnet_full):
     first_conv = next(l for l in lines if "igemm_conv_linear" in l)
     assert "tile=" in first_conv and f"C={c.stage_out_ch[0]} " in first_conv
     assert net.profile_read_launches() == ""
+
+
+def test_supernet_profiler_table_has_the_scheduler_properties(torch_mod, resnet_full):
+    """The latency table the profiler measures with the real kernels: positive entries, latency rising
+    with the batch and with the subnet (the properties the paper's scheduler builds its latency buckets
+    on), and a slack pick that meets its deadline."""
+    from paper_2312_16733_amd import profiler
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    cfgs = [C[0], C[7], C[15]]
+    batches = (1, 8, 32)
+    dev = torch.device("cuda:0")
+
+    def make_inputs(c, b):
+        return torch.from_numpy(synth.make_inputs(spec, b, c.in_h, c.in_w, 41)).to(torch.bfloat16).to(dev)
+
+    say("profiling 3 cfgs x 3 batch sizes")
+    table = profiler.profile_latency(net, spec, cfgs, make_inputs, batches, reps=5)
+    assert table.shape == (3, 3) and (table > 0).all()
+    props = profiler.check_properties(table, slack=0.10)
+    assert props["p1_violations"] == 0 and props["p2_violations"] == 0 and props["p3_violations"] == 0, (table, props)
+    bks = profiler.latency_buckets(table, batches, 6)
+    assert sum(len(b.choices) for b in bks) == 9
+    choice = profiler.pick(bks, float(table.max()) * 1.01)
+    assert choice is not None and choice[2] <= table.max() * 1.01
