@@ -216,6 +216,28 @@ sna_status sna_subnet_tune(sna_supernet* net,
                            const void* inputs_dev, float* logits_dev,
                            void* hidden_dev, void* hip_stream);
 
+/* SubnetNorm calibration of one subnet (the paper computes every subnet's
+ * normalisation statistics by forward passes over data before serving; section
+ * "SubNetAct", SubnetNorm paragraph).  Runs cfg on n_requests inputs; every
+ * SubnetNorm layer the subnet executes takes the per-channel mean and population
+ * variance of its own input (the layer's convolution output in fp32, over all
+ * requests and pixels), writes them as fp32 into row cfg->subnet_id of stats_dev
+ * (fields mean and var, the layer's leading active channels; gamma, beta, other
+ * rows and the layers of skipped blocks are left alone), refreshes the folded
+ * scale / shift kept in the workspace, and normalises with the values as stored,
+ * so that a later sna_subnet_forward of the same cfg on the same inputs returns
+ * the same logits (to summation order of the squeeze-excite pool where a family
+ * has one).  stats_dev must be the device table given to
+ * sna_supernet_load (the caller still owns it; this is the one call that writes
+ * it).  logits_dev [n_requests][n_classes] receives that forward's logits.
+ * The fp32 outputs of the layers launched together (a block's last convolution
+ * and its projection shortcut) must fit the 64 MiB scratch region of the
+ * workspace: SNA_E_WORKSPACE otherwise, before anything runs (use a smaller batch).  SNA_E_ARCH for families
+ * without SubnetNorm.  Not for use concurrently with other calls on the handle. */
+sna_status sna_subnet_calibrate(sna_supernet* net, const sna_subnet_cfg* cfg,
+                                int32_t n_requests, const void* inputs_dev,
+                                void* stats_dev, float* logits_dev, void* hip_stream);
+
 /* Number of layer shapes with a measured tile variant on this handle. */
 int32_t sna_tuned_count(const sna_supernet* net);
 

@@ -6,6 +6,8 @@ headers, helpers or tables, and neither imports the other.
 
   inplace.forward             subnet served in place on the max-size tensors
                               (LayerSelect / WeightSlice / SubnetNorm as stated)
+  inplace.calibrate           the same forward filling the subnet's SubnetNorm
+                              mean / variance rows from the batch it sees
   standalone.extract_subnet,
   standalone.standalone_forward   the definition: copy the slices out, run the
                               resulting ordinary network with library ops
@@ -18,8 +20,8 @@ rounding closed forms.  Whole-network logits have no published values to pin
 against: the paper prints none.
 """
 from . import primitives, inplace, standalone, brute
-from .inplace import forward
+from .inplace import forward, calibrate
 from .standalone import extract_subnet, standalone_forward
 
-__all__ = ["primitives", "inplace", "standalone", "brute", "forward",
+__all__ = ["primitives", "inplace", "standalone", "brute", "forward", "calibrate",
            "extract_subnet", "standalone_forward"]

@@ -145,3 +145,14 @@ def forward(spec, weights, stats, cfg, x, mode=None, **kw):
     mode = mode or spec.dtype
     rd = P.ROUND[mode]
     return _FAMILY[spec.family](spec, weights, stats, cfg, rd(x), rd, **kw)
+
+
+def calibrate(spec, weights, stats, cfg, x, mode=None):
+    """SubnetNorm calibration of subnet `cfg` on the batch x: one forward in which every SubnetNorm
+    layer the subnet runs takes its mean / variance row from the activations it sees (gamma and beta
+    stay).  Returns (copy of stats with row cfg.subnet_id filled in, logits of that forward).
+    A later forward(spec, weights, new_stats, cfg, x) reproduces these logits exactly."""
+    new = {k: np.array(v, copy=True) for k, v in stats.items()}
+    wrapped = {k: P.CalibrationTable(v) for k, v in new.items()}
+    logits = forward(spec, weights, wrapped, cfg, x, mode)
+    return new, logits

@@ -116,12 +116,31 @@ def linear_sliced(x, w_max, n_out: int, bias=None):
 EPS = 1e-5
 
 
+class CalibrationTable:
+    """A layer's statistics table [n_subnets][4][C_max] that is being calibrated: subnet_norm fills
+    the mean and variance of row i from the very batch it is about to normalise."""
+
+    def __init__(self, table):
+        self.table = table
+
+
 def subnet_norm(x, stats_layer, subnet_id: int):
     """SubnetNorm (SubnetNorm paragraph): look up the statistics stored for
     (subnet i, layer j) and normalise with them.  stats_layer is the layer's
     table [n_subnets][4][C_max] = (mean, var, gamma, beta); the leading
-    x.shape[-1] entries of row i are used:  gamma*(x-mean)/sqrt(var+eps)+beta."""
+    x.shape[-1] entries of row i are used:  gamma*(x-mean)/sqrt(var+eps)+beta.
+
+    Calibration (the paper computes each subnet's statistics by forward passes
+    over data before serving): when the table comes wrapped in CalibrationTable,
+    the per-channel mean and (population) variance of x over batch and pixels
+    are stored into row i first, in the table's own precision, and the
+    normalisation then reads them back like any later forward would."""
     c = x.shape[-1]
+    if isinstance(stats_layer, CalibrationTable):
+        stats_layer = stats_layer.table
+        flat = _f64(x).reshape(-1, c)
+        stats_layer[subnet_id, 0, :c] = flat.mean(axis=0)
+        stats_layer[subnet_id, 1, :c] = flat.var(axis=0)
     mean, var, gamma, beta = (stats_layer[subnet_id, f, :c].astype(np.float64) for f in range(4))
     return gamma * (x - mean) / np.sqrt(var + EPS) + beta
 

@@ -83,6 +83,7 @@ def lib():
     L.sna_subnet_forward.argtypes = [vp, C.POINTER(SubnetCfgC), i32, C.POINTER(i32), i32, vp, vp, vp, vp]
     L.sna_subnet_forward.restype = i32
     L.sna_subnet_tune.argtypes = L.sna_subnet_forward.argtypes; L.sna_subnet_tune.restype = i32
+    L.sna_subnet_calibrate.argtypes = [vp, vp, i32, vp, vp, vp, vp]; L.sna_subnet_calibrate.restype = i32
     L.sna_tuned_count.argtypes = [vp]; L.sna_tuned_count.restype = i32
     L.sna_tuning_export.argtypes = [vp, C.c_char_p, i64]; L.sna_tuning_export.restype = i64
     L.sna_tuning_import.argtypes = [vp, C.c_char_p, i64]; L.sna_tuning_import.restype = i32
@@ -273,6 +274,26 @@ class Supernet:
     def tune(self, cfgs, req_cfg, inputs, hidden=None, stream=None):
         """One forward that also measures the tile variants of every layer shape it meets."""
         return self.forward(cfgs, req_cfg, inputs, hidden=hidden, stream=stream, tune=True)
+
+    def calibrate(self, cfg, inputs, logits=None, stream=None):
+        """SubnetNorm calibration of one cfg on `inputs` (device tensor, requests concatenated): fills
+        row cfg.subnet_id of the resident statistics table; returns that forward's logits."""
+        torch = self.torch
+        cfgs_c = self.prepare_cfgs([cfg])
+        assert inputs.dtype == self.act_dtype and inputs.is_contiguous() and inputs.device == self.device
+        n = inputs.shape[0]
+        if logits is None:
+            logits = torch.empty((n, self.spec.n_classes), dtype=torch.float32, device=self.device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        _check(lib().sna_subnet_calibrate(self.handle, cfgs_c, n, inputs.data_ptr(), self.stats.data_ptr(),
+                                          logits.data_ptr(), stream))
+        return logits
+
+    def stats_table(self) -> dict:
+        """The resident statistics table read back: name -> fp32 [n_subnets][4][C_max]."""
+        host = self.stats.cpu().numpy().reshape(self.n_subnets, 4, -1)
+        return {ni.name.decode(): host[:, :, ni.offset:ni.offset + ni.channels].copy() for ni in norm_infos(self.arch)}
 
     def tuned_count(self):
         return int(lib().sna_tuned_count(self.handle))

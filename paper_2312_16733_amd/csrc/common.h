@@ -21,7 +21,8 @@ enum KClass {
   KC_FOLD = 8,       // SubnetNorm statistics folding (load time)
   KC_KREDUCE = 9,    // sum of the K-chunk partials + fused epilogue of a split igemm
   KC_STEMPOOL = 10,  // fused 7x7/2 stem conv + SubnetNorm + ReLU + 3x3/2 max pool
-  KC_COUNT = 11
+  KC_CALIB = 11,     // SubnetNorm calibration: channel statistics and the normalise pass
+  KC_COUNT = 12
 };
 
 // ---- one problem of a grouped launch -------------------------------------------------------
@@ -86,6 +87,7 @@ struct DwProblem {
   // every block writes the sums of its own outputs, as stored, per channel: pool_part[n][block][C].
   float* pool_part;     // nullptr: flat grid, no pool
   int bpr;
+  int raw_out;          // calibration: y is fp32 and gets the bare sums (no SubnetNorm, no activation)
   int tile_start, tiles;
 };
 struct DwGroupArgs { int n; DwProblem p[SNA_MAX_GROUPS]; };
@@ -145,6 +147,24 @@ struct PadItem { unsigned long src, dst; unsigned long pixels; };   // byte offs
 #define SNA_PAD_ITEMS 128
 struct PadArgs { const void* src; void* dst; int n; int c_in; PadItem it[SNA_PAD_ITEMS]; };
 
+// SubnetNorm calibration of one layer: per-channel mean and population variance of its raw conv output
+// [M][K] fp32 over the M rows (all requests, all pixels), written into the caller's statistics table
+// (fp32) and folded into this layer's scale / shift from the values as stored.
+struct NormCalArgs {
+  const float* raw; int M, K;
+  float* part; int nrb;            // [nrb][K][3] (count, mean, M2) of row blocks of SNA_CAL_ROWS rows
+  float* mean; float* var;         // rows of the statistics table, at this layer's offset
+  const float* gamma; const float* beta;
+  float* scale; float* shift;      // folded table, same offset
+};
+#define SNA_CAL_ROWS 256
+// y = act(scale * raw + shift (+ res)) in the family's storage dtype: what the fused epilogues do, on the
+// raw conv output kept by a calibration pass
+struct NormApplyArgs {
+  const float* raw; const float* scale; const float* shift; const void* res; void* y;
+  int M, K, act, res_after_act, res_stride, y_stride;
+};
+
 // fp32 partial sums of split reductions: fixed region at the end of the workspace
 constexpr size_t kPartialBytes = (size_t)64 << 20;
 
@@ -158,6 +178,8 @@ hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(const PoolGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_gap(const PoolGroupArgs& a, int dtype, hipStream_t s);
 hipError_t launch_depthwise(const DwGroupArgs& a, hipStream_t s);
+hipError_t launch_norm_calibrate(const NormCalArgs& a, hipStream_t s);
+hipError_t launch_norm_apply(const NormApplyArgs& a, int dtype, hipStream_t s);
 int depthwise_pool_blocks(int Ho, int Wo, int C);   // blocks per request of a depthwise layer with the fused pool
 hipError_t launch_se(const SeGroupArgs& a, hipStream_t s);
 hipError_t launch_layernorm(const LnGroupArgs& a, hipStream_t s);

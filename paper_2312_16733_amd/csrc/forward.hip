@@ -381,6 +381,64 @@ struct Fwd {
     emit(PlanOp::DIRECT, 0, T().arch.dtype, KC_DIRECT, flops, bytes, a);
   }
 
+  // ---- SubnetNorm calibration -----------------------------------------------------------------
+  // Statistics-table rows behind a folded scale pointer: (subnet id, offset of the layer in a row).
+  void norm_rows(const float* scale, NormCalArgs& c) const {
+    const size_t rl = (size_t)T().row_len, idx = (size_t)(scale - net->folded);
+    const size_t id = idx / (2 * rl), off = idx % (2 * rl);
+    float* row = net->stats_mut + id * 4 * rl + off;
+    c.mean = row; c.var = row + rl; c.gamma = row + 2 * rl; c.beta = row + 3 * rl;
+    c.scale = net->folded + id * 2 * rl + off; c.shift = c.scale + rl;
+  }
+  // After the raw fp32 output of a layer is in `raw`: measure it, store the statistics, normalise.
+  void calibrate_layer(const float* raw, float* part, int M, int K, const float* scale, const void* res, void* y,
+                       int act, int res_after_act, int res_stride, int y_stride) {
+    NormCalArgs c;
+    memset(&c, 0, sizeof(c));
+    c.raw = raw; c.M = M; c.K = K; c.part = part; c.nrb = (M + SNA_CAL_ROWS - 1) / SNA_CAL_ROWS;
+    norm_rows(scale, c);
+    emit(PlanOp::NORMCAL, 0, 0, KC_CALIB, 0, 4.0 * M * K, c);
+    NormApplyArgs ap;
+    memset(&ap, 0, sizeof(ap));
+    ap.raw = raw; ap.scale = c.scale; ap.shift = c.shift; ap.res = res; ap.y = y;
+    ap.M = M; ap.K = K; ap.act = act; ap.res_after_act = res_after_act; ap.res_stride = res_stride; ap.y_stride = y_stride;
+    emit(PlanOp::NORMAPPLY, 0, T().arch.dtype, KC_CALIB, 0, (4.0 + 2.0 * esz()) * M * K, ap);
+  }
+  // Room for a layer's raw output and its row-block partials in the fp32 scratch region (which the
+  // split reductions, switched off while calibrating, otherwise use).
+  bool cal_scratch(char*& cur, int M, int K, float*& raw, float*& part) {
+    const size_t raw_b = align_up((size_t)M * K * 4, 256);
+    const size_t part_b = align_up((size_t)((M + SNA_CAL_ROWS - 1) / SNA_CAL_ROWS) * K * 3 * 4, 256);
+    if ((size_t)(cur - net->partials) + raw_b + part_b > kPartialBytes) { err = hipErrorOutOfMemory; return false; }
+    raw = (float*)cur; part = (float*)(cur + raw_b);
+    cur += raw_b + part_b;
+    return true;
+  }
+  // A conv slot while calibrating: layers with SubnetNorm run bare (no scale / shift / activation /
+  // residual, fp32 output), then each is measured and normalised; the others run as usual.
+  void calibrate_convs(std::vector<ConvProblem>& ps, bool direct) {
+    std::vector<ConvProblem> plain, bare, orig;
+    char* cur = net->partials;
+    std::vector<std::pair<float*, float*>> bufs;
+    for (ConvProblem& p : ps) {
+      if (!p.scale) { plain.push_back(p); continue; }
+      float *raw, *part;
+      if (!cal_scratch(cur, p.M, p.K, raw, part)) return;
+      orig.push_back(p);
+      ConvProblem b = p;
+      b.scale = nullptr; b.shift = nullptr; b.res = nullptr; b.act = SNA_ACT_NONE; b.res_after_act = 0;
+      b.y = raw; b.y_stride = p.K; b.out_fp32 = 1;
+      bare.push_back(b);
+      bufs.push_back({raw, part});
+    }
+    if (direct) { run_direct(plain); run_direct(bare); } else { run_igemm(plain); run_igemm(bare); }
+    for (size_t i = 0; i < orig.size(); ++i) {
+      const ConvProblem& p = orig[i];
+      calibrate_layer(bufs[i].first, bufs[i].second, p.M, p.K, p.scale, p.res, p.y, p.act, p.res_after_act, p.res_stride,
+                      p.y_stride);
+    }
+  }
+
   // One conv slot over all groups.  `fill` returns false for groups that skip the slot.
   void conv_slot(bool direct, const std::function<bool(Group&, ConvProblem&)>& fill) {
     std::vector<ConvProblem> ps;
@@ -389,6 +447,7 @@ struct Fwd {
       memset(&p, 0, sizeof(p));
       if (fill(g, p)) ps.push_back(p);
     }
+    if (net->calibrating) { calibrate_convs(ps, direct); return; }
     if (direct) run_direct(ps); else run_igemm(ps);
   }
 
@@ -404,6 +463,7 @@ struct Fwd {
         memset(&p, 0, sizeof(p));
         if ((which == 0 ? fill_a : fill_b)(g, p)) ps.push_back(p);
       }
+    if (net->calibrating) { calibrate_convs(ps, false); return; }
     if (ps.size() > SNA_MAX_GROUPS) {      // would not fit one launch anyway
       std::vector<ConvProblem> a(ps.begin(), ps.begin() + ps.size() / 2), b(ps.begin() + ps.size() / 2, ps.end());
       run_igemm(a);
@@ -455,7 +515,22 @@ struct Fwd {
       bytes += 2.0 * p.N * p.C * ((double)p.H * p.W + (double)p.Ho * p.Wo) + 2.0 * p.k * p.k * p.C + 8.0 * p.C;
       a.p[a.n++] = p;
     }
-    if (a.n) emit(PlanOp::DW, 0, 0, KC_DEPTHWISE, flops, bytes, a);
+    if (!a.n) return;
+    if (!net->calibrating) { emit(PlanOp::DW, 0, 0, KC_DEPTHWISE, flops, bytes, a); return; }
+    // calibration: bare fp32 sums first, then statistics and the normalise pass per layer
+    DwGroupArgs bare = a;
+    char* cur = net->partials;
+    std::vector<std::pair<float*, float*>> bufs;
+    for (int i = 0; i < a.n; ++i) {
+      float *raw, *part;
+      if (!cal_scratch(cur, a.p[i].N * a.p[i].Ho * a.p[i].Wo, a.p[i].C, raw, part)) return;
+      bare.p[i].y = raw; bare.p[i].raw_out = 1; bare.p[i].pool_part = nullptr; bare.p[i].bpr = 0;
+      bufs.push_back({raw, part});
+    }
+    emit(PlanOp::DW, 0, 0, KC_DEPTHWISE, flops, bytes, bare);
+    for (int i = 0; i < a.n; ++i)
+      calibrate_layer(bufs[i].first, bufs[i].second, a.p[i].N * a.p[i].Ho * a.p[i].Wo, a.p[i].C, a.p[i].scale, nullptr,
+                      a.p[i].y, a.p[i].act, 0, a.p[i].C, a.p[i].C);
   }
   // Depthwise WeightSlice: leading C channels, centre k x k window of the stored kernel.
   void slice_dw(DwProblem& p, const sna_tensor_info& ti, int k, int stride) {
@@ -615,6 +690,7 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
   for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = 8; }     // channel-padded inputs
   bool fused_stem = a.dtype == SNA_DTYPE_BF16 && tensor("stem.w").dims[1] == 7 && tensor("stem.w").dims[2] == 7;
   for (const Group& g : groups) fused_stem = fused_stem && g.cfg->stage_out_ch[0] <= 64;
+  fused_stem = fused_stem && !net->calibrating;          // calibration needs the stem's bare output
   if (fused_stem) {
     // stem conv + SubnetNorm + ReLU + max pool in one kernel: the conv output stays in LDS
     StemPoolArgs sa;
@@ -781,13 +857,20 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
         slice_dw(p, tensor(pre + "dw.w"), g.cfg->block_kernel[s][j], st);
         p.scale = scale_of(pre + "sn2", g.cfg->subnet_id); p.shift = shift_of(pre + "sn2", g.cfg->subnet_id);
         p.act = act; p.y = g.buf[3];
-        if (a.stage_se[s]) {                                    // the gate's average pool rides on this launch
+        if (a.stage_se[s] && !net->calibrating) {               // the gate's average pool rides on this launch
           p.pool_part = g.small;
           p.bpr = depthwise_pool_blocks(p.Ho, p.Wo, p.C);
         }
         return true;
       });
       if (a.stage_se[s]) {
+        if (net->calibrating)                                  // the pool could not ride on a bare-output launch
+          pool_slot(false, [&](Group& g, PoolProblem& p) {
+            if (!on(g)) return false;
+            p.x = g.buf[3]; p.N = g.n; p.H = out_size(g.H, 3, st); p.W = out_size(g.W, 3, st);
+            p.C = g.cfg->block_mid_ch[s][j]; p.y = g.small; p.out_fp32 = 1;
+            return true;
+          });
         se_slot([&](Group& g, SeProblem& p) {
           if (!on(g)) return false;
           const int m = g.cfg->block_mid_ch[s][j];
@@ -799,6 +882,7 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
           const int ho = out_size(g.H, 3, st), wo = out_size(g.W, 3, st);
           p.N = g.n; p.HW = ho * wo; p.C = m; p.Q = g.cfg->block_aux_ch[s][j];
           p.pool_segs = depthwise_pool_blocks(ho, wo, m); p.inv_hw = 1.f / (float)p.HW;
+          if (net->calibrating) { p.pool_segs = 1; p.inv_hw = 1.f; }      // g.small holds the mean itself
           p.pooled = g.small;                                  // written by the depthwise launch above
           p.hidden = g.small + (size_t)p.pool_segs * g.n * m;
           return true;
@@ -990,6 +1074,8 @@ static hipError_t run_op(const PlanOp& op, hipStream_t s) {
     case PlanOp::COPY: return launch_copy(*(const CopyArgs*)a, s);
     case PlanOp::PAD: return launch_pad_input(*(const PadArgs*)a, s);
     case PlanOp::STEMPOOL: return launch_stem_pool(*(const StemPoolArgs*)a, s);
+    case PlanOp::NORMCAL: return launch_norm_calibrate(*(const NormCalArgs*)a, s);
+    case PlanOp::NORMAPPLY: return launch_norm_apply(*(const NormApplyArgs*)a, op.flag, s);
   }
   return hipErrorInvalidValue;
 }
@@ -1038,6 +1124,8 @@ static void visit_io_pointers(const PlanOp& op, F&& f) {
       for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
       break;
     }
+    case PlanOp::NORMCAL: break;          // reads the scratch region, writes the statistics table
+    case PlanOp::NORMAPPLY: { const NormApplyArgs* a = (const NormApplyArgs*)base; at(&a->res); at(&a->y); break; }
   }
 }
 
@@ -1240,7 +1328,7 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   // The launch list depends on the routing, on the cfgs it names, on whether hidden states are
   // wanted and on the tuning state; caller buffers only enter through patched pointer fields.
   std::string key;
-  const bool use_cache = net->plan_cache_on && !net->tuning;
+  const bool use_cache = net->plan_cache_on && !net->tuning && !net->calibrating;
   if (use_cache) {
     key.reserve((size_t)n_requests * 4 + 1024);
     const int32_t head[3] = {n_requests, hidden_dev ? 1 : 0, net->split_mode};
@@ -1356,7 +1444,7 @@ sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t
 
 static const char* kClassNames[SNA_N_KCLASS] = {"igemm_conv_linear", "direct_conv", "depthwise", "pool",
                                                 "squeeze_excite", "layernorm", "attention", "copy",
-                                                "fold_stats", "k_chunk_reduce", "stem_pool", ""};
+                                                "fold_stats", "k_chunk_reduce", "stem_pool", "calibration"};
 const char* sna_profile_class_name(int32_t k) { return (k >= 0 && k < SNA_N_KCLASS) ? kClassNames[k] : ""; }
 
 sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs, const int32_t* req_cfg,
@@ -1432,6 +1520,27 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
   if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return fail(SNA_E_HIP, "stream synchronize");
   // leave the caller's outputs as a plain forward would
   return sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
+}
+
+sna_status sna_subnet_calibrate(sna_supernet* net, const sna_subnet_cfg* cfg, int32_t n_requests, const void* inputs_dev,
+                                void* stats_dev, float* logits_dev, void* hip_stream) {
+  if (!net || !cfg || !inputs_dev || !stats_dev || !logits_dev) return fail(SNA_E_NULL, "NULL argument");
+  if (net->T.row_len == 0) return fail(SNA_E_ARCH, "this architecture has no SubnetNorm layers");
+  if ((const float*)stats_dev != net->stats) return fail(SNA_E_BATCH, "stats_dev is not the table this SuperNet was loaded with");
+  if (n_requests < 1) return fail(SNA_E_BATCH, "calibration needs at least one request");
+  std::vector<int32_t> route((size_t)n_requests, 0);
+  const int split_was = net->split_mode;
+  net->calibrating = true;
+  net->stats_mut = (float*)stats_dev;
+  net->split_mode = 1;                       // the fp32 scratch region holds the layers' raw outputs
+  sna_status st = sna_subnet_forward(net, cfg, 1, route.data(), n_requests, inputs_dev, logits_dev, nullptr, hip_stream);
+  net->calibrating = false;
+  net->stats_mut = nullptr;
+  net->split_mode = split_was;
+  if (st == SNA_E_HIP && strstr(sna_last_error(), "out of memory"))
+    return fail(SNA_E_WORKSPACE, "calibration batch too large: a layer's fp32 output does not fit the %zu MiB scratch region",
+                kPartialBytes >> 20);
+  return st;
 }
 
 int32_t sna_tuned_count(const sna_supernet* net) { return net ? (int32_t)(net->tuned.size() + net->tuned_split.size()) : 0; }

@@ -51,7 +51,7 @@ struct Group {
 
 // One recorded kernel launch of a forward call.
 struct PlanOp {
-  enum Type { IGEMM, KREDUCE, DIRECT, MAXPOOL, GAP, DW, SE, LN, ATTN, COPY, PAD, STEMPOOL } type;
+  enum Type { IGEMM, KREDUCE, DIRECT, MAXPOOL, GAP, DW, SE, LN, ATTN, COPY, PAD, STEMPOOL, NORMCAL, NORMAPPLY } type;
   int variant = 0, flag = 0;         // igemm: tile variant, chunked kernel; direct / pool: dtype
   int kc = 0;                        // kernel class for the per-launch timing
   double flops = 0, bytes = 0;
@@ -85,6 +85,10 @@ struct sna_supernet {
   std::map<std::array<int, 6>, int> tuned;
   // measured for a chunked layer shape: 1 = one block per K chunk plus the reduction kernel is faster
   std::map<std::array<int, 6>, int> tuned_split;
+  // SubnetNorm calibration in progress: every layer with statistics keeps its raw output, measures it
+  // and writes the subnet's row of the caller's table (stats_mut) before normalising
+  bool calibrating = false;
+  float* stats_mut = nullptr;
   int forced_variant = -1;           // >= 0: every igemm launch uses this tile variant (test knob)
   bool tuning = false;               // the forward in progress measures shapes it has no entry for
   // launch lists of recent forward calls, replayed when the same cfgs / routing come again

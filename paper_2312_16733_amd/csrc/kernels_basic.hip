@@ -285,6 +285,170 @@ hipError_t launch_pad_input(const PadArgs& a, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// SubnetNorm calibration (the paper computes every subnet's statistics by forward passes before
+// serving).  Per channel, mean and sum of squared deviations are carried as (n, mean, M2) and merged
+// pairwise with Chan's formula, always in the same order: a thread takes its rows in groups of 8
+// (group mean, then squared deviations from it, all 8 values in registers), merges group after
+// group, the 4 row lanes of a block merge in lane order, the row blocks in lane-strided order by 16
+// lanes that merge in lane order.  The variance stored is the population one (M2 / n).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void chan_merge(float& n, float& mean, float& m2, float nb, float meanb, float m2b) {
+  if (nb == 0.f) return;
+  const float nt = n + nb, d = meanb - mean;
+  mean += d * (nb / nt);
+  m2 += m2b + d * d * (n * nb / nt);
+  n = nt;
+}
+
+__global__ __launch_bounds__(256) void channel_stats_partial_kernel(const NormCalArgs a) {
+  __shared__ float red[3][4][64];
+  const int ch = blockIdx.y * 64 + (threadIdx.x & 63), rl = threadIdx.x >> 6;
+  const int r0 = blockIdx.x * SNA_CAL_ROWS;
+  const int r1 = r0 + SNA_CAL_ROWS < a.M ? r0 + SNA_CAL_ROWS : a.M;
+  float n = 0.f, mean = 0.f, m2 = 0.f;
+  if (ch < a.K) {
+    const float* src = a.raw + ch;
+    for (int r = r0 + rl; r < r1; r += 32) {      // 8 rows of this lane: r, r+4, ..., r+28
+      float v[8];
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int rr = r + 4 * j;
+        const bool in = rr < r1;
+        v[j] = in ? src[(long)rr * a.K] : 0.f;
+        cnt += in;
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += v[j];
+      const float nb = (float)cnt, gm = sum / nb;
+      float g2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float d = (r + 4 * j < r1) ? v[j] - gm : 0.f;
+        g2 = fmaf(d, d, g2);
+      }
+      chan_merge(n, mean, m2, nb, gm, g2);
+    }
+  }
+  red[0][rl][threadIdx.x & 63] = n; red[1][rl][threadIdx.x & 63] = mean; red[2][rl][threadIdx.x & 63] = m2;
+  __syncthreads();
+  if (rl == 0 && ch < a.K) {
+#pragma unroll
+    for (int j = 1; j < 4; ++j) chan_merge(n, mean, m2, red[0][j][threadIdx.x], red[1][j][threadIdx.x], red[2][j][threadIdx.x]);
+    float* o = a.part + ((long)blockIdx.x * a.K + ch) * 3;
+    o[0] = n; o[1] = mean; o[2] = m2;
+  }
+}
+
+__device__ __forceinline__ void chan_merge_d(double& n, double& mean, double& m2, double nb, double meanb, double m2b) {
+  if (nb == 0) return;
+  const double nt = n + nb, d = meanb - mean;
+  mean += d * (nb / nt);
+  m2 += m2b + d * d * (n * nb / nt);
+  n = nt;
+}
+
+// 16 channels per block, 16 lanes per channel over the row blocks; double precision from here on.
+__global__ __launch_bounds__(256) void channel_stats_final_kernel(const NormCalArgs a) {
+  __shared__ double red[3][16][16];
+  const int cl = threadIdx.x & 15, lane = threadIdx.x >> 4;
+  const int ch = blockIdx.x * 16 + cl;
+  double n = 0, mean = 0, m2 = 0;
+  if (ch < a.K)
+    for (int b = lane; b < a.nrb; b += 16) {
+      const float* q = a.part + ((long)b * a.K + ch) * 3;
+      chan_merge_d(n, mean, m2, q[0], q[1], q[2]);
+    }
+  red[0][lane][cl] = n; red[1][lane][cl] = mean; red[2][lane][cl] = m2;
+  __syncthreads();
+  if (lane != 0 || ch >= a.K) return;
+  for (int j = 1; j < 16; ++j) chan_merge_d(n, mean, m2, red[0][j][cl], red[1][j][cl], red[2][j][cl]);
+  const float mean_f = (float)mean, var_f = (float)(m2 / n);
+  a.mean[ch] = mean_f;
+  a.var[ch] = var_f;
+  // folded from the values as stored, exactly like the load-time fold
+  const double sc = (double)a.gamma[ch] / sqrt((double)var_f + 1e-5);
+  a.scale[ch] = (float)sc;
+  a.shift[ch] = (float)((double)a.beta[ch] - (double)mean_f * sc);
+}
+
+hipError_t launch_norm_calibrate(const NormCalArgs& a, hipStream_t s) {
+  if (a.M < 1 || a.K < 1 || a.nrb != (a.M + SNA_CAL_ROWS - 1) / SNA_CAL_ROWS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(channel_stats_partial_kernel, dim3(a.nrb, (a.K + 63) / 64), dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(channel_stats_final_kernel, dim3((a.K + 15) / 16), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// One element per thread (any K and strides), or, where K and both row strides are multiples of 4
+// and the pointers aligned for it, four consecutive channels per thread with 16-byte loads.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void norm_apply_kernel(const NormApplyArgs a) {
+  const unsigned idx = blockIdx.x * 256u + threadIdx.x;     // in units of V elements; the launcher bounds it
+  const unsigned kv = (unsigned)a.K / V;
+  const unsigned m = idx / kv;
+  if (m >= (unsigned)a.M) return;
+  const int k = (int)(idx - m * kv) * V;
+  float v[V], sc[V], sh[V], r[V];
+  const float* raw = a.raw + (long)m * a.K + k;
+  if constexpr (V == 4) {
+    const float4 q = *(const float4*)raw, s4 = *(const float4*)(a.scale + k), h4 = *(const float4*)(a.shift + k);
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    sc[0] = s4.x; sc[1] = s4.y; sc[2] = s4.z; sc[3] = s4.w;
+    sh[0] = h4.x; sh[1] = h4.y; sh[2] = h4.z; sh[3] = h4.w;
+  } else {
+    v[0] = raw[0]; sc[0] = a.scale[k]; sh[0] = a.shift[k];
+  }
+  if (a.res) {
+    const T* rp = (const T*)a.res + (long)m * a.res_stride + k;
+    if constexpr (V == 4 && sizeof(T) == 2) {
+      const uint2 u = *(const uint2*)rp;
+      r[0] = __uint_as_float(u.x << 16); r[1] = __uint_as_float(u.x & 0xffff0000u);
+      r[2] = __uint_as_float(u.y << 16); r[3] = __uint_as_float(u.y & 0xffff0000u);
+    } else {
+#pragma unroll
+      for (int j = 0; j < V; ++j) r[j] = ld_f32<T>(rp + j);
+    }
+  }
+  T* yp = (T*)a.y + (long)m * a.y_stride + k;
+  float w[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    w[j] = fmaf(v[j], sc[j], sh[j]);
+    if (a.res && !a.res_after_act) w[j] += r[j];
+    w[j] = apply_act(w[j], a.act);
+    if (a.res && a.res_after_act) w[j] += r[j];
+  }
+  if constexpr (V == 4 && sizeof(T) == 2) {
+    *(uint2*)yp = make_uint2(pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]));
+  } else if constexpr (V == 4) {
+    *(float4*)yp = make_float4(w[0], w[1], w[2], w[3]);
+  } else {
+    st_f32<T>(yp, w[0]);
+  }
+}
+
+hipError_t launch_norm_apply(const NormApplyArgs& a, int dtype, hipStream_t s) {
+  const long total = (long)a.M * a.K;
+  if (total < 1 || total >= (1l << 32) - 256) return hipErrorInvalidValue;
+  const size_t esz = dtype == SNA_DTYPE_FP32 ? 4 : 2;
+  const bool vec = a.K % 4 == 0 && a.res_stride % 4 == 0 && a.y_stride % 4 == 0 && (uintptr_t)a.raw % 16 == 0 &&
+                   (uintptr_t)a.scale % 16 == 0 && (uintptr_t)a.shift % 16 == 0 && (uintptr_t)a.y % (4 * esz) == 0 &&
+                   (uintptr_t)a.res % (4 * esz) == 0;
+  const unsigned blocks = (unsigned)(((vec ? total / 4 : total) + 255) / 256);
+  if (dtype == SNA_DTYPE_FP32) {
+    if (vec) hipLaunchKernelGGL((norm_apply_kernel<float, 4>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((norm_apply_kernel<float, 1>), dim3(blocks), dim3(256), 0, s, a);
+  } else {
+    if (vec) hipLaunchKernelGGL((norm_apply_kernel<bf16_t, 4>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((norm_apply_kernel<bf16_t, 1>), dim3(blocks), dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // SubnetNorm folding at load time: stats [n_subnets][4][row_len] (mean, var, gamma, beta) ->
 // folded [n_subnets][2][row_len] with scale = gamma / sqrt(var + eps), shift = beta - mean*scale.
 // ---------------------------------------------------------------------------------------------

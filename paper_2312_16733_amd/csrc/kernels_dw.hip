@@ -133,6 +133,16 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DwGroupArgs args) 
           }
     }
   }
+  if (p.raw_out) {
+    float* yr = (float*)p.y + (((long)n * p.Ho + pp) * p.Wo) * p.C + c8 * 8;
+#pragma unroll
+    for (int o = 0; o < DW_TW; ++o) {
+      if (q0 + o >= p.Wo) break;
+      *(float4*)(yr + (long)(q0 + o) * p.C) = make_float4(acc[o][0], acc[o][1], acc[o][2], acc[o][3]);
+      *(float4*)(yr + (long)(q0 + o) * p.C + 4) = make_float4(acc[o][4], acc[o][5], acc[o][6], acc[o][7]);
+    }
+    return;
+  }
   float sc[8], sh[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { sc[e] = p.scale[c8 * 8 + e]; sh[e] = p.shift[c8 * 8 + e]; }
