@@ -157,3 +157,24 @@ def test_calibration_rejects_what_it_cannot_do(torch_mod):
         assert all(np.array_equal(before[k], after[k]) for k in before)     # refused before anything was launched
     finally:
         net.close()
+
+
+def test_calibrate_all_helper(torch_mod):
+    """The offline helper calibrates every cfg in turn; afterwards each row reproduces on a plain forward."""
+    import paper_2312_16733_amd as sna
+    from paper_2312_16733_amd.calibrate import calibrate_all
+    torch = torch_mod
+    spec = synth.TinySpec()
+    W, S, C = setup(spec, 8)
+    net = sna.Supernet(spec, W, S, 8, 8)
+    try:
+        xs = {c.subnet_id: to_dev(torch, spec, synth.make_inputs(spec, 6, c.in_h, c.in_w, 40 + c.subnet_id)) for c in C}
+        times = calibrate_all(net, C, lambda c, b: xs[c.subnet_id], 6)
+        assert len(times) == len(C) and all(t > 0 for t in times)
+        table = net.stats_table()
+        for name, v in table.items():
+            assert np.all(np.isfinite(v)), name
+            assert not np.array_equal(v[:, 0:2], S[name][:, 0:2]), name       # rows were rewritten
+            assert np.array_equal(v[:, 2:4], S[name][:, 2:4]), name           # gamma / beta untouched
+    finally:
+        net.close()

@@ -623,3 +623,48 @@ def test_supernet_profiler_table_has_the_scheduler_properties(torch_mod, resnet_
     assert sum(len(b.choices) for b in bks) == 9
     choice = profiler.pick(bks, float(table.max()) * 1.01)
     assert choice is not None and choice[2] <= table.max() * 1.01
+
+
+# ------------------------------------------------------------------ other seeds than the standing ones
+@pytest.mark.parametrize("k", [5, 17, 29])
+def test_fresh_seeds_small_shapes(torch_mod, k):
+    """Every family at small shapes with weight, cfg and input seeds the other tests do not use, random
+    batch sizes 1..6 per cfg, plus one mixed call of 13 requests over the cfgs that share a resolution."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    torch = torch_mod
+    cases = [("tiny", synth.TinySpec(), 8, "fp32"),
+             ("resnet-small", SMALL_RESNET, 10, "bf16"),
+             ("mbv3-small", synth.MBV3Spec(res_choices=(40, 48, 57, 64)), 10, "bf16"),
+             ("tf-small", synth.TransformerSpec(n_classes=40, hidden=256, n_heads=4, head_dim=64, ffn=512, max_layers=4,
+                                                seq_len=16 + (k * 8) % 113, depth_choices=(2, 3, 4)), 8, "bf16")]
+    for j, (name, spec, n_cfg, mode) in enumerate(cases):
+        wseed, cseed = 100 * (2 * j + 1) + k, 100 * (2 * j + 2) + k
+        W, S, C = setup(spec, n_cfg, wseed=wseed, cseed=cseed)
+        net = sna.Supernet(spec, W, S, n_cfg, 16)
+        rng = np.random.default_rng(cseed)
+        worst = 0.0
+        try:
+            for c in C:
+                b = int(rng.integers(1, 7))
+                x = synth.make_inputs(spec, b, c.in_h, c.in_w, int(rng.integers(1, 1000)))
+                say(name, "seeds", wseed, cseed, "cfg", c.subnet_id, "batch", b)
+                got = run_single(torch, net, spec, c, x)
+                e, _ = check_parity(got, oracle.forward(spec, W, S, c, x), mode, f"{name} cfg {c.subnet_id}")
+                worst = max(worst, e)
+            byres = {}
+            for c in C:
+                byres.setdefault((c.in_h, c.in_w), []).append(c)
+            res, cs = max(byres.items(), key=lambda kv: len(kv[1]))
+            if len(cs) > 1:
+                route = rng.integers(0, len(cs), 13).astype(np.int32)
+                x = synth.make_inputs(spec, 13, res[0], res[1], 77)
+                got = net.forward(cs, route, to_dev(torch, spec, x)).cpu().numpy()
+                torch.cuda.synchronize()
+                for r in range(13):
+                    e, _ = check_parity(got[r:r + 1], oracle.forward(spec, W, S, cs[route[r]], x[r:r + 1]), mode,
+                                        f"{name} mixed request {r}")
+                    worst = max(worst, e)
+        finally:
+            net.close()
+        say("  ", name, "worst rel err %.3e" % worst)
