@@ -170,6 +170,7 @@ constexpr size_t kPartialBytes = (size_t)64 << 20;
 
 // ---- launchers (defined in the .hip files) ---------------------------------------------------
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s);
+bool igemm_variant_ok(int variant, const ConvProblem& p);   // can this tile variant run this problem (some take 3x3 stride-1 layers only)
 hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s);
 hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s);
 void igemm_tile_shape(int variant, int* bm, int* bn);

@@ -184,6 +184,7 @@ struct Fwd {
     int best = -1;
     *best_ms = 0.f;
     for (int v = 0; v < igemm_num_variants() && err == hipSuccess; ++v) {
+      if (!igemm_variant_ok(v, q)) continue;
       ConvGroupArgs a;
       a.n = 1;
       a.p[0] = q;
@@ -290,7 +291,8 @@ struct Fwd {
       }
       auto it = net->tuned.find(tune_key(q, q.parts));
       if (it != net->tuned.end()) var[i] = it->second;
-      if (net->forced_variant >= 0) var[i] = net->forced_variant;
+      if (net->forced_variant >= 0 && igemm_variant_ok(net->forced_variant, q)) var[i] = net->forced_variant;
+      if (!igemm_variant_ok(var[i], q)) var[i] = pick_variant(q.M, q.K, q.C * q.R * q.S);
       place(q, var[i]);
     }
     if ((unify || n > 1) && !net->tuning) {
@@ -307,7 +309,10 @@ struct Fwd {
         }
         if (lead < 0) continue;
         for (size_t i = 0; i < n; ++i)
-          if ((ps[i].parts == 1 && chunks[i] > 1) == (chunked == 1)) { var[i] = var[lead]; place(ps[i], var[i]); }
+          if ((ps[i].parts == 1 && chunks[i] > 1) == (chunked == 1) && igemm_variant_ok(var[lead], ps[i])) {
+            var[i] = var[lead];
+            place(ps[i], var[i]);
+          }
       }
     }
     if (err != hipSuccess) return;
@@ -1194,7 +1199,7 @@ static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t 
     if (e != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(e));
     if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
       ProfRec rec{op.kc, a, b, describe_op(op)};
-      if (op.type == PlanOp::IGEMM) { rec.igemm = true; rec.key = lead_key(op); }
+      if (op.type == PlanOp::IGEMM) { rec.igemm = true; rec.key = lead_key(op); rec.variant = op.variant; }
       net->prof_recs.push_back(std::move(rec));
       net->prof_flops[op.kc] += op.flops;
       net->prof_bytes[op.kc] += op.bytes;
@@ -1483,7 +1488,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
       if (st != SNA_OK) break;
       std::map<std::array<int, 6>, double> sum;
       for (const ProfRec& r : net->prof_recs) {
-        if (!r.igemm) continue;
+        if (!r.igemm || r.variant != v) continue;       // a variant that cannot run this shape was not applied
         float ms = 0;
         hipError_t e = hipEventSynchronize(r.b);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);

@@ -31,6 +31,7 @@ sna_status fail(sna_status st, const char* fmt, ...);
 struct ProfRec {
   int kc; hipEvent_t a, b; std::string what;
   bool igemm = false;                // a matrix-kernel launch: `key` is the tuning key of its problem with the most work
+  int variant = -1;                  // the tile variant that launch ran with
   std::array<int, 6> key{};
 };
 

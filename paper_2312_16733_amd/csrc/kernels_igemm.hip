@@ -55,6 +55,8 @@ struct IgemmCfg {
   static constexpr int SMEM = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
 };
 
+__device__ __forceinline__ unsigned long long low_bits(int n) { return n >= 64 ? ~0ull : (1ull << n) - 1ull; }   // n >= 0
+
 __device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
   u32x4 v;
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -128,6 +130,8 @@ void igemm_kernel(const ConvGroupArgs args) {
   // rows this thread fetches: byte offset of the window's first tap and which taps are in range
   int a_base[A_IT];
   unsigned long long a_mask[A_IT];      // bit rs set: tap rs of this row's window is inside the image
+  unsigned long long tap_rows = 0;      // bit r * S for every window row r (uniform)
+  for (int r = 0; r < p.R; ++r) tap_rows |= 1ull << (r * S);
   const bool pointwise = RS == 1 && p.stride == 1 && p.pad == 0;   // output pixel m reads input pixel m
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
@@ -147,12 +151,14 @@ void igemm_kernel(const ConvGroupArgs args) {
         const int pp = t - n * p.Ho;
         const int ih0 = pp * p.stride - p.pad, iw0 = q * p.stride - p.pad;
         a_base[i] = ((n * H + ih0) * Wd + iw0) * C * 2;
-        unsigned colm = 0;                // taps of one window row that fall inside the image
-        for (int s = 0; s < S; ++s)
-          if (iw0 + s >= 0 && iw0 + s < Wd) colm |= 1u << s;
+        // taps inside the image: columns [s_lo, s_hi) of window rows [r_lo, r_hi), without loops
+        const int s_lo = iw0 < 0 ? -iw0 : 0, s_hi = Wd - iw0 < S ? Wd - iw0 : S;
+        const int r_lo = ih0 < 0 ? -ih0 : 0, r_hi = H - ih0 < p.R ? H - ih0 : p.R;
         unsigned long long mk = 0;
-        for (int r = 0; r < p.R; ++r)
-          if (ih0 + r >= 0 && ih0 + r < H) mk |= (unsigned long long)colm << (r * S);
+        if (s_hi > s_lo && r_hi > r_lo) {
+          const unsigned long long colm = low_bits(s_hi) & ~low_bits(s_lo);
+          mk = colm * (tap_rows & low_bits(r_hi * S) & ~low_bits(r_lo * S));      // one copy of colm per window row
+        }
         a_mask[i] = mk;
       }
     }
@@ -435,6 +441,353 @@ void igemm_kernel(const ConvGroupArgs args) {
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------
+// 3x3 stride-1 pad-1 convolution with the activation operand resident in LDS ("slab").
+//
+// The implicit GEMM above fetches every activation row of a tile once per tap: nine trips through
+// the texture path, each a 16-byte gather at a pixel stride that is rarely a multiple of the cache
+// line.  For a 3x3 stride-1 layer the BM consecutive output pixels of a tile read, over all nine
+// taps, only the BM + 2 W + 2 consecutive input pixels around them (NHWC, images back to back), so
+// this kernel loads that slab once, linearly, and the matrix pipe takes its A fragments from it at
+// tap-shifted addresses; only the weights stream through the ring.  A tap that falls outside the
+// image (or a row past M) reads a 16-byte block of zeros instead.  The slab's pixel stride is the
+// channel count rounded up to an odd number of 16-byte units (the spare unit is zero-filled), which
+// spreads consecutive pixels over the LDS banks.  The reduction runs in the same order and in the
+// same 16-element MFMA slices as the implicit GEMM (tap-major, then channels), and chunk sums
+// are folded at the same steps, so the output has the same bits.
+// ---------------------------------------------------------------------------------------------
+constexpr int slab_units(int bm, int w, int c8, int nthreads) {
+  const int c8p = c8 | 1;
+  const int units = (bm + 2 * w + 2) * c8p + 1;          // + the block of zeros
+  return (units + nthreads - 1) / nthreads * nthreads;
+}
+
+template <int BM, int BN, int WARPS_M, int WARPS_N, int NS, bool CHUNKED>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N, BM * BN > 128 * 128 ? 1 : 2)
+void conv3_slab_kernel(const ConvGroupArgs args) {
+#if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
+  using Cfg = IgemmCfg<BM, BN, WARPS_M, WARPS_N, NS>;
+  constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::NTHREADS;
+  constexpr int B_IT = Cfg::B_IT, L = B_IT;                // ring loads per thread per stage: weights only
+  constexpr int RING_STAGE_B = BN * ROW_B;
+  static_assert(BN % Cfg::PASS_ROWS == 0, "every wave issues the same number of loads");
+  static_assert((NS - 2) * L < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const unsigned lds0 = (unsigned)(size_t)(lds_char*)smem;
+
+  const int per_xcd = gridDim.x >> 3;
+  const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile_id >= args.total_tiles) return;
+  ConvProblem p = args.p[0];
+  if (args.n > 1) {
+    const int g = find_problem(args, tile_id);
+    if (g > 0) p = args.p[g];
+  }
+  const int local = tile_id - p.tile_start;
+  const int tn = local % p.tiles_n, tm = local / p.tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tid = threadIdx.x;
+  const int wm = wave / WARPS_N, wn = wave % WARPS_N;
+  const int lrow = tid >> 3;
+  const int kc = (tid & 7) ^ ((lrow >> 1) & 7);
+  const int C = p.C, H = p.H, Wd = p.W, C8 = p.C8;
+  const int C8p = C8 | 1;                                  // slab pixel stride in 16-byte units, odd
+  const int P = BM + 2 * Wd + 2;                           // slab pixels
+  const int units = P * C8p;                               // unit `units` is the block of zeros
+  const int n_it = (units + 1 + NT - 1) / NT;
+  const unsigned ring0 = lds0 + (unsigned)n_it * NT * 16;
+
+  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, (int)p.w_bytes, 0x00020000);
+  constexpr unsigned OOB = 0x80000000u;
+
+  // ---- slab: input pixels m0 - W - 1 .. m0 + BM + W of the flattened (n, y, x) order, once ------
+  {
+    const int pix0 = m0 - Wd - 1, n_pix = p.N * H * Wd;
+    const unsigned magic = 0xFFFFFFFFu / (unsigned)C8p + 1u;        // e / C8p = mulhi(e, magic) for e < 2^16 * C8p
+    lds_char* const dst = (lds_char*)smem + wave * 64 * 16;
+#pragma unroll 1
+    for (int it = 0; it < n_it; ++it) {
+      const unsigned e = (unsigned)(it * NT + tid);
+      const int px = (int)__umulhi(e, magic), c = (int)e - px * C8p;
+      const int gp = pix0 + px;
+      const bool ok = c < C8 && px < P && gp >= 0 && gp < n_pix;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dst + it * NT * 16, 16, ok ? (unsigned)((gp * C + c * 8) * 2) : OOB,
+                                               0, 0, 0);
+    }
+  }
+
+  // ---- weights: ring of NS stages, as in the implicit GEMM ------------------------------------
+  int b_base[B_IT];
+  unsigned b_ok = 0;
+#pragma unroll
+  for (int j = 0; j < B_IT; ++j) {
+    const int row = lrow + Cfg::PASS_ROWS * j;
+    const int k = n0 + row;
+    if (row < BN && k < p.K) b_ok |= 1u << j;
+    b_base[j] = k * p.wk * 2;
+  }
+  int rs = kc / C8;
+  int c8 = kc - rs * C8;
+  const int KT = (p.K8 + 7) >> 3;
+  lds_char* const dma_b = (lds_char*)smem + n_it * NT * 16 + (wave * 8) * ROW_B;
+  unsigned dma_off[L];
+  auto locate = [&]() {
+    const bool u_ok = rs < 9;
+    const int r = (rs * 11) >> 5, s = rs - r * 3;              // rs / 3 for rs < 32
+    const int tw = (r * p.wr + s * p.ws + c8 * 8) * 2;
+#pragma unroll
+    for (int j = 0; j < B_IT; ++j) dma_off[j] = (u_ok && ((b_ok >> j) & 1u)) ? (unsigned)(b_base[j] + tw) : OOB;
+  };
+  locate();
+  auto issue = [&](int stage) {
+#pragma unroll
+    for (int j = 0; j < B_IT; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, dma_b + stage * RING_STAGE_B + Cfg::PASS_ROWS * j * ROW_B, 16,
+                                               dma_off[j], 0, 0, 0);
+    c8 += 8;
+    if (c8 >= C8) {
+      do { c8 -= C8; ++rs; } while (c8 >= C8);
+      locate();
+    } else {
+#pragma unroll
+      for (int j = 0; j < L; ++j) dma_off[j] += BK * 2;
+    }
+  };
+
+  // ---- this lane's A rows: slab address of tap (0, 0) and which taps lie inside the image ------
+  const int frag_row = lane & 31, frag_hi = lane >> 5, frag_sw = (frag_row >> 1) & 7;
+  unsigned a_row[TM], a_taps[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = wm * WTM + i * 32 + frag_row;
+    const int m = m0 + row;
+    a_row[i] = lds0 + (unsigned)(row * C8p) * 16;
+    unsigned mk = 0;
+    if (m < p.M) {
+      const int t = (int)__umulhi((unsigned)m, p.magic_wo);            // W >= 2 for a padded 3x3 to make sense
+      const int xq = m - t * Wd;
+      const int n = H == 1 ? t : (int)__umulhi((unsigned)t, p.magic_ho);
+      const int yq = t - n * H;
+      unsigned colm = 0;
+#pragma unroll
+      for (int s = 0; s < 3; ++s)
+        if (xq + s - 1 >= 0 && xq + s - 1 < Wd) colm |= 1u << s;
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+        if (yq + r - 1 >= 0 && yq + r - 1 < H) mk |= colm << (3 * r);
+    }
+    a_taps[i] = mk;
+  }
+  const unsigned zero_addr = lds0 + (unsigned)units * 16;
+  // reduction position of this lane's unit in the slice about to be read: tap (ar, as), octet ac8
+  int ars = frag_hi / C8, ac8 = frag_hi - ars * C8;
+  int a_r = 0, a_s = ars;                                   // ars <= 1 here
+  unsigned a_addr[TM];
+  auto a_next = [&]() {                                     // addresses of the current slice, then advance by two units
+    const unsigned tap = (unsigned)(((a_r * Wd + a_s) * C8p + ac8) * 16);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const bool ok = ars < 9 && ((a_taps[i] >> ars) & 1u);
+      a_addr[i] = ok ? a_row[i] + tap : zero_addr;
+    }
+    ac8 += 2;
+    while (ac8 >= C8) {
+      ac8 -= C8; ++ars; ++a_s;
+      if (a_s == 3) { a_s = 0; ++a_r; }
+    }
+  };
+
+  f32x16 acc[TM][TN];
+  unsigned frag_off[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) frag_off[ks] = (unsigned)(((ks * 2 + frag_hi) ^ frag_sw) * 16);
+  const unsigned b_lane = ring0 + (wn * WTN + frag_row) * ROW_B;
+
+  // All fragment reads of a step are requested up front (LDS returns them in order) and each
+  // 16-wide slice waits only for its own: a wave then has up to 4 (TM + TN) reads in flight, which
+  // the LDS needs to come near its bandwidth (measured: 105 B/clk/CU with 4 reads in flight per wave,
+  // 208 with 8 on 8 waves); one slice ahead leaves the step bound by LDS latency.
+  constexpr int NSL = BK / 16, RPS = TM + TN;               // slices per step, reads per slice
+  auto compute = [&](int stage, const bool fresh) {
+    const unsigned bb = b_lane + stage * RING_STAGE_B;
+    u32x4 af[NSL][TM], bfr[NSL][TN];
+#pragma unroll
+    for (int ks = 0; ks < NSL; ++ks) {                      // every read of the step up front, in slice order
+      a_next();
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[ks][i] = lds_read_b128(a_addr[i], 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[ks][j] = lds_read_b128(bb + frag_off[ks], j * 32 * ROW_B);
+    }
+    auto slice = [&](auto ks_c) {
+      constexpr int ks = decltype(ks_c)::value;
+      constexpr int later = (NSL - 1 - ks) * RPS;
+      __builtin_amdgcn_s_waitcnt(0xc07f | ((later > 15 ? 15 : later) << 8));      // lgkmcnt(later)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) asm volatile("" : "+v"(af[ks][i]));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bfr[ks][j]));
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks == 0 && fresh) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks][i]),
+                                                                __builtin_bit_cast(bf16x8, bfr[ks][j]), zero, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks][i]),
+                                                                __builtin_bit_cast(bf16x8, bfr[ks][j]), acc[i][j], 0, 0, 0);
+      }
+    };
+    static_assert(NSL == 4, "four slices per step");
+    slice(std::integral_constant<int, 0>{});
+    slice(std::integral_constant<int, 1>{});
+    slice(std::integral_constant<int, 2>{});
+    slice(std::integral_constant<int, 3>{});
+  };
+
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+    if (st < KT) issue(st);
+
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  float sc[TN], sh[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int k = n0 + wn * WTN + j * 32 + col_l;
+    sc[j] = (p.scale && k < p.K) ? p.scale[k] : 1.f;
+    sh[j] = (p.shift && k < p.K) ? p.shift[k] : 0.f;
+  }
+
+  f32x16 tot[CHUNKED ? TM : 1][CHUNKED ? TN : 1];
+  int to_fold = p.kt_chunk;
+  if (CHUNKED) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[i][j][v] = 0.f;
+  }
+  int stage = 0, fill = NS - 1;
+  bool fresh = true;
+  for (int kt = 0; kt < KT; ++kt) {
+    // the slab's loads were issued ahead of every ring load, and loads complete in order
+    if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    if (kt + NS - 1 < KT) issue(fill);
+    compute(stage, fresh);
+    fresh = false;
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+    if (CHUNKED && --to_fold == 0 && kt + 1 < KT) {
+      to_fold = p.kt_chunk;
+      fresh = true;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tot[i][j][v] = tot[i][j][v] + acc[i][j][v];
+    }
+  }
+  __syncthreads();
+
+  // ---- epilogue: as in the implicit GEMM (bf16 output, no split parts) -------------------------
+  float* epi = (float*)smem + wave * 32 * Cfg::EPI_STRIDE;
+  constexpr int OCT = WTN / 8;
+  constexpr int PAIRS = 32 * OCT / 64;
+  auto epilogue = [&](auto act_c, auto res_c) {
+    constexpr int ACT = decltype(act_c)::value, RES = decltype(res_c)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] =
+              fmaf(CHUNKED ? tot[i][j][v] + acc[i][j][v] : acc[i][j][v], sc[j], sh[j]);
+      uint4 r4[PAIRS];
+      if (RES != 0) {
+#pragma unroll
+        for (int t = 0; t < PAIRS; ++t) {
+          const int id = t * 64 + lane;
+          const int row = id / OCT, oct = id - row * OCT;
+          const int m = m0 + wm * WTM + i * 32 + row;
+          const int k = n0 + wn * WTN + oct * 8;
+          r4[t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
+                                       : make_uint4(0, 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int t = 0; t < PAIRS; ++t) {
+        const int id = t * 64 + lane;
+        const int row = id / OCT, oct = id - row * OCT;
+        const int m = m0 + wm * WTM + i * 32 + row;
+        const int k = n0 + wn * WTN + oct * 8;
+        const float4 v0 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8);
+        const float4 v1 = *(const float4*)(epi + row * Cfg::EPI_STRIDE + oct * 8 + 4);
+        float val[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        float rv[8];
+        if (RES != 0) {
+          const unsigned ru[4] = {r4[t].x, r4[t].y, r4[t].z, r4[t].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            rv[2 * e] = __uint_as_float(ru[e] << 16);
+            rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
+          }
+        }
+        if (RES == 1) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] += rv[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], ACT);
+        if (RES == 2) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] += rv[e];
+        }
+        if (m < p.M && k < p.K) {
+          uint4 o;
+          o.x = pack_bf16x2(val[0], val[1]);
+          o.y = pack_bf16x2(val[2], val[3]);
+          o.z = pack_bf16x2(val[4], val[5]);
+          o.w = pack_bf16x2(val[6], val[7]);
+          *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  };
+  using std::integral_constant;
+#define SNA_EPI(A, R) epilogue(integral_constant<int, A>{}, integral_constant<int, R>{})
+  const int res_mode = p.res ? (p.res_after_act ? 2 : 1) : 0;
+  if (p.act == SNA_ACT_RELU) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_RELU, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_RELU, 1); else SNA_EPI(SNA_ACT_RELU, 2);
+  } else if (p.act == SNA_ACT_NONE) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_NONE, 0); else SNA_EPI(SNA_ACT_NONE, 1);
+  } else if (p.act == SNA_ACT_HSWISH) {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_HSWISH, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_HSWISH, 1); else SNA_EPI(SNA_ACT_HSWISH, 2);
+  } else {
+    if (res_mode == 0) SNA_EPI(SNA_ACT_GELU, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_GELU, 1); else SNA_EPI(SNA_ACT_GELU, 2);
+  }
+#undef SNA_EPI
+#endif
+}
+
 // Second half of a reduction that was split over blocks: adds the fp32 chunk sums in chunk order,
 // then SubnetNorm scale/shift, residual and activation exactly as the fused epilogue does, so
 // the output has the same bits as the one-block-per-tile path.  One thread = 8 channels of a row.
@@ -525,13 +878,20 @@ hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-struct Variant { int bm, bn, threads, smem, ns, stage_bytes, epi_bytes; void (*fn)(const ConvGroupArgs); void (*fn_chunked)(const ConvGroupArgs); };
+struct Variant {
+  int bm, bn, threads, smem, ns, stage_bytes, epi_bytes;
+  void (*fn)(const ConvGroupArgs); void (*fn_chunked)(const ConvGroupArgs);
+  bool slab;             // conv3_slab_kernel: 3x3 stride-1 layers only; stage_bytes is the weight ring's
+};
 #define SNA_VARIANT(BM, BN, WM, WN, NS) \
   { BM, BN, 64 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
-    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, false>, igemm_kernel<BM, BN, WM, WN, NS, true, false> }
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, false>, igemm_kernel<BM, BN, WM, WN, NS, true, false>, false }
 #define SNA_WS_VARIANT(BM, BN, WM, WN, NS) \
   { BM, BN, 128 * WM * WN, IgemmCfg<BM, BN, WM, WN, NS>::SMEM, NS, IgemmCfg<BM, BN, WM, WN, NS>::STAGE_B, \
-    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, true>, igemm_kernel<BM, BN, WM, WN, NS, true, true> }
+    IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, igemm_kernel<BM, BN, WM, WN, NS, false, true>, igemm_kernel<BM, BN, WM, WN, NS, true, true>, false }
+#define SNA_SLAB_VARIANT(BM, BN, WM, WN, NS) \
+  { BM, BN, 64 * WM * WN, 0, NS, BN * ROW_B, IgemmCfg<BM, BN, WM, WN, NS>::EPI_BYTES, \
+    conv3_slab_kernel<BM, BN, WM, WN, NS, false>, conv3_slab_kernel<BM, BN, WM, WN, NS, true>, true }
 // 0..6 are the variants the shape heuristic chooses from; the rest are reached through tuning only.
 static const Variant kVariants[] = {
     SNA_VARIANT(128, 128, 2, 2, 2), SNA_VARIANT(128, 64, 2, 2, 2), SNA_VARIANT(128, 96, 4, 1, 2),
@@ -540,6 +900,9 @@ static const Variant kVariants[] = {
     SNA_WS_VARIANT(64, 64, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 3), SNA_WS_VARIANT(128, 64, 2, 2, 3),
     SNA_WS_VARIANT(128, 96, 4, 1, 3), SNA_WS_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 32, 4, 1, 2),
     SNA_WS_VARIANT(32, 128, 1, 4, 4), SNA_VARIANT(128, 192, 2, 2, 2), SNA_WS_VARIANT(128, 192, 2, 2, 3),
+    // 16..: 3x3 stride-1 layers with the activation slab in LDS
+    SNA_SLAB_VARIANT(128, 128, 2, 2, 2), SNA_SLAB_VARIANT(128, 64, 2, 2, 2), SNA_SLAB_VARIANT(128, 96, 4, 1, 2),
+    SNA_SLAB_VARIANT(64, 64, 2, 2, 2), SNA_SLAB_VARIANT(64, 128, 1, 4, 2), SNA_SLAB_VARIANT(128, 96, 4, 1, 3),
 #ifdef SNA_EXTRA_VARIANTS
     SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
     SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 4),
@@ -549,11 +912,27 @@ static const Variant kVariants[] = {
 #endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kLdsMax = 160 * 1024;
 
 int igemm_num_variants() { return kNumVariants; }
 void igemm_tile_shape(int variant, int* bm, int* bn) {
   *bm = kVariants[variant].bm;
   *bn = kVariants[variant].bn;
+}
+
+// LDS a slab variant needs for one problem (all ring stages)
+static int slab_smem(const Variant& v, const ConvProblem& p, int stages) {
+  const int tiles = slab_units(v.bm, p.W, p.C8, v.threads) * 16 + stages * v.stage_bytes;
+  return tiles > v.epi_bytes ? tiles : v.epi_bytes;
+}
+
+bool igemm_variant_ok(int variant, const ConvProblem& p) {
+  if (variant < 0 || variant >= kNumVariants) return false;
+  const Variant& v = kVariants[variant];
+  if (!v.slab) return true;
+  return p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.parts == 1 && !p.out_fp32 && p.W >= 2 &&
+         p.Ho == p.H && p.Wo == p.W && (long)(v.bm + 2 * p.W + 2) * (p.C8 | 1) < (1 << 20) &&
+         slab_smem(v, p, v.ns) <= kLdsMax;
 }
 
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s) {
@@ -563,7 +942,7 @@ hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipSt
   const Variant& v = kVariants[variant];
   void (*fn)(const ConvGroupArgs) = chunked ? v.fn_chunked : v.fn;
   if (!attr_done[variant][chunked]) {
-    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.smem);
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.slab ? kLdsMax : v.smem);
     if (e != hipSuccess) return e;
     attr_done[variant][chunked] = true;
   }
@@ -576,7 +955,15 @@ hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipSt
     if (kt > kt_max) kt_max = kt;
   }
   const int stages = kt_max < v.ns ? kt_max : v.ns;
-  const int smem = stages * v.stage_bytes > v.epi_bytes ? stages * v.stage_bytes : v.epi_bytes;
+  int smem = stages * v.stage_bytes > v.epi_bytes ? stages * v.stage_bytes : v.epi_bytes;
+  if (v.slab) {
+    smem = 0;
+    for (int i = 0; i < a.n; ++i) {
+      if (!igemm_variant_ok(variant, a.p[i])) return hipErrorInvalidValue;
+      const int need = slab_smem(v, a.p[i], v.ns);
+      if (need > smem) smem = need;
+    }
+  }
   const int blocks = (a.total_tiles + 7) / 8 * 8;
   hipLaunchKernelGGL(fn, dim3(blocks), dim3(v.threads), smem, s, a);
   return hipGetLastError();
