@@ -176,7 +176,7 @@ def main():
                 "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(),
                 "algorithmic_bytes_per_launch": ig["bytes"] / max(ig["launches"], 1),
                 "frac_of_hbm_peak": (ig["bytes"] / (ig["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS) if ig["ms"] > 0 else 0.0,
-                "kernel": "igemm_kernel (all tile variants)",
+                "kernel": "igemm_kernel + conv3_slab_kernel (all tile variants)",
                 "avg_launch_us": 1e3 * ig["ms"] / max(ig["launches"], 1),
                 "launches": ig["launches"],
                 "hbm_gbs_algorithmic": ig["bytes"] / (ig["ms"] * 1e-3) / 1e9 if ig["ms"] > 0 else 0.0,
