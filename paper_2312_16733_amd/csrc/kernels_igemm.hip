@@ -350,6 +350,26 @@ void igemm_kernel(const ConvGroupArgs args) {
   auto epilogue = [&](auto act_c, auto res_c, auto f32_c) {
     constexpr int ACT = decltype(act_c)::value, RES = decltype(res_c)::value;
     constexpr bool F32 = decltype(f32_c)::value;
+    // Residual rows.  With several 32-row strips per wave they are all requested up front, so that
+    // one round trip runs under the staging of the first strip instead of one per strip; with a
+    // single strip the request goes after the staging writes, when the accumulators' registers are free.
+    constexpr bool RES_UP_FRONT = TM > 1;
+    uint4 r4[TM][PAIRS];
+    auto load_res = [&](int i) {
+#pragma unroll
+      for (int t = 0; t < PAIRS; ++t) {
+        const int id = t * 64 + lane;
+        const int row = id / OCT, oct = id - row * OCT;
+        const int m = m0 + wm * WTM + i * 32 + row;
+        const int k = n0 + wn * WTN + oct * 8;
+        r4[i][t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
+                                        : make_uint4(0, 0, 0, 0);
+      }
+    };
+    if (RES != 0 && RES_UP_FRONT) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) load_res(i);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -358,19 +378,7 @@ void igemm_kernel(const ConvGroupArgs args) {
         for (int v = 0; v < 16; ++v)
           epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] =
               fmaf(CHUNKED ? tot[i][j][v] + acc[i][j][v] : acc[i][j][v], sc[j], sh[j]);
-      // residual rows of this strip, requested before the staged values are read back
-      uint4 r4[PAIRS];
-      if (RES != 0) {
-#pragma unroll
-        for (int t = 0; t < PAIRS; ++t) {
-          const int id = t * 64 + lane;
-          const int row = id / OCT, oct = id - row * OCT;
-          const int m = m0 + wm * WTM + i * 32 + row;
-          const int k = n0 + wn * WTN + oct * 8;
-          r4[t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
-                                       : make_uint4(0, 0, 0, 0);
-        }
-      }
+      if (RES != 0 && !RES_UP_FRONT) load_res(i);
       // wave-private region: the wave's own LDS writes are visible to its later reads
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
@@ -386,7 +394,7 @@ void igemm_kernel(const ConvGroupArgs args) {
         float val[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
         float rv[8];
         if (RES != 0) {
-          const unsigned ru[4] = {r4[t].x, r4[t].y, r4[t].z, r4[t].w};
+          const unsigned ru[4] = {r4[i][t].x, r4[i][t].y, r4[i][t].z, r4[i][t].w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             rv[2 * e] = __uint_as_float(ru[e] << 16);
@@ -709,6 +717,26 @@ void conv3_slab_kernel(const ConvGroupArgs args) {
   constexpr int PAIRS = 32 * OCT / 64;
   auto epilogue = [&](auto act_c, auto res_c) {
     constexpr int ACT = decltype(act_c)::value, RES = decltype(res_c)::value;
+    // Residual rows.  With several 32-row strips per wave they are all requested up front, so that
+    // one round trip runs under the staging of the first strip instead of one per strip; with a
+    // single strip the request goes after the staging writes, when the accumulators' registers are free.
+    constexpr bool RES_UP_FRONT = TM > 1;
+    uint4 r4[TM][PAIRS];
+    auto load_res = [&](int i) {
+#pragma unroll
+      for (int t = 0; t < PAIRS; ++t) {
+        const int id = t * 64 + lane;
+        const int row = id / OCT, oct = id - row * OCT;
+        const int m = m0 + wm * WTM + i * 32 + row;
+        const int k = n0 + wn * WTN + oct * 8;
+        r4[i][t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
+                                        : make_uint4(0, 0, 0, 0);
+      }
+    };
+    if (RES != 0 && RES_UP_FRONT) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) load_res(i);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -717,18 +745,7 @@ void conv3_slab_kernel(const ConvGroupArgs args) {
         for (int v = 0; v < 16; ++v)
           epi[(8 * (v >> 2) + row_l + (v & 3)) * Cfg::EPI_STRIDE + j * 32 + col_l] =
               fmaf(CHUNKED ? tot[i][j][v] + acc[i][j][v] : acc[i][j][v], sc[j], sh[j]);
-      uint4 r4[PAIRS];
-      if (RES != 0) {
-#pragma unroll
-        for (int t = 0; t < PAIRS; ++t) {
-          const int id = t * 64 + lane;
-          const int row = id / OCT, oct = id - row * OCT;
-          const int m = m0 + wm * WTM + i * 32 + row;
-          const int k = n0 + wn * WTN + oct * 8;
-          r4[t] = (m < p.M && k < p.K) ? *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k)
-                                       : make_uint4(0, 0, 0, 0);
-        }
-      }
+      if (RES != 0 && !RES_UP_FRONT) load_res(i);
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_s_waitcnt(0xc07f);        // lgkmcnt(0)
       __builtin_amdgcn_wave_barrier();
@@ -743,7 +760,7 @@ void conv3_slab_kernel(const ConvGroupArgs args) {
         float val[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
         float rv[8];
         if (RES != 0) {
-          const unsigned ru[4] = {r4[t].x, r4[t].y, r4[t].z, r4[t].w};
+          const unsigned ru[4] = {r4[i][t].x, r4[i][t].y, r4[i][t].z, r4[i][t].w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             rv[2 * e] = __uint_as_float(ru[e] << 16);
