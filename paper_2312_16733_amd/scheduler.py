@@ -19,8 +19,9 @@ smallest profiled batch that holds them; a query whose deadline has already pass
 the head of the queue is dropped and counts as a miss.  Subnet index stands in for accuracy (no
 trained weights): "accuracy rank" is index / (S - 1).
 
-This module is plain host code: the workers are modelled by the measured table, nothing here touches
-the GPU.
+The policies, traces and event loop are plain host code.  Workers are either modelled by the
+measured table or, with `GpuExecutor`, are the library itself: every dispatched batch runs through
+the forward entry point and occupies the worker for the time it took.
 """
 from __future__ import annotations
 
@@ -138,12 +139,15 @@ def accelerating_trace(rate1: float, rate2: float, tau: float, cv2: float, durat
 
 
 # ---- router + workers ---------------------------------------------------------------------------
-def simulate(policy: Policy, arrivals_s: np.ndarray, slo_ms: float, n_workers: int = 1) -> dict:
+def simulate(policy: Policy, arrivals_s: np.ndarray, slo_ms: float, n_workers: int = 1, executor=None) -> dict:
     """Discrete-event run: queries arrive at arrivals_s with deadline arrival + slo; whenever a worker
     is free and the EDF queue is not empty the policy picks (b, s) from the head query's slack, the
-    batch is dequeued in deadline order and occupies the worker for the profiled latency.  Returns SLO
-    attainment over all arrivals, the mean accuracy rank over served queries and the decision log
-    (time s, slack ms, batch, subnet, queries taken)."""
+    batch is dequeued in deadline order and occupies the worker for the profiled latency.  With an
+    `executor(subnet row, batch column, queries taken) -> milliseconds` the batch is really run (see
+    `GpuExecutor`) and the worker is occupied for the time it took; the policy still decides on the
+    profiled table, as the paper's scheduler does.  Returns SLO attainment over all arrivals, the mean
+    accuracy rank over served queries and the decision log (time s, slack ms, batch, subnet, queries
+    taken)."""
     table, batches = policy.table, policy.batches
     n_sub = table.shape[0]
     slo = slo_ms * 1e-3
@@ -171,7 +175,8 @@ def simulate(policy: Policy, arrivals_s: np.ndarray, slo_ms: float, n_workers: i
         j, i = policy.choose(theta_ms)
         take = min(batches[j], len(queue))
         j_eff = bisect.bisect_left(batches, take)           # smallest profiled batch that holds them
-        done = now + table[i, j_eff] * 1e-3
+        service_ms = table[i, j_eff] if executor is None else executor(i, j_eff, take)
+        done = now + service_ms * 1e-3
         for _ in range(take):
             deadline, _qid = heapq.heappop(queue)
             served += 1
@@ -181,6 +186,33 @@ def simulate(policy: Policy, arrivals_s: np.ndarray, slo_ms: float, n_workers: i
         log.append((now, theta_ms, batches[j], i, take))
     return {"queries": n, "served": served, "dropped": dropped, "slo_attainment": met / n if n else 1.0,
             "mean_accuracy_rank": rank_sum / served if served else 0.0, "decisions": log}
+
+
+class GpuExecutor:
+    """Runs the chosen control tuple on the resident SuperNet and returns the time it took (events on
+    torch's current stream): the worker of the paper's architecture, driven by `simulate` in virtual
+    time.  A batch of `take` queries runs as the first `take` requests of the profiled batch's inputs."""
+
+    def __init__(self, net, spec, cfgs, batches, make_inputs):
+        self.net, self.torch, self.batches = net, net.torch, tuple(batches)
+        self.cfgs = [net.prepare_cfgs([c]) for c in cfgs]
+        self.inputs = [make_inputs(c, self.batches[-1]) for c in cfgs]
+        self.logits = self.torch.empty((self.batches[-1], spec.n_classes), dtype=self.torch.float32, device=self.inputs[0].device)
+        self.calls = 0
+        self.busy_ms = 0.0
+
+    def __call__(self, i: int, j: int, take: int) -> float:
+        torch = self.torch
+        route = np.zeros(take, np.int32)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        self.net.forward(self.cfgs[i], route, self.inputs[i][:take], logits=self.logits[:take])
+        e1.record()
+        e1.synchronize()
+        ms = float(e0.elapsed_time(e1))
+        self.calls += 1
+        self.busy_ms += ms
+        return ms
 
 
 def main():
@@ -199,6 +231,7 @@ def main():
     ap = argparse.ArgumentParser(description="SlackFit / MaxBatch / MaxAcc on the measured latency table")
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--duration", type=float, default=2.0, help="seconds of simulated trace")
+    ap.add_argument("--live-duration", type=float, default=0.25, help="seconds of trace for the runs that drive the GPU")
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
     spec = synth.ResNetSpec()
@@ -215,7 +248,6 @@ def main():
 
     batches = profiler.POW2_BATCHES
     full = profiler.profile_latency(net, spec, C, make_inputs, batches)
-    net.close()
     # a set ordered in both directions, as the binary searches need: pareto at the largest batch, then
     # rows that break the order at batch 1 are dropped too
     front = profiler.pareto_subset(full)
@@ -241,6 +273,28 @@ def main():
         for pol in (SlackFit(table, batches), MaxBatch(table, batches), MaxAcc(table, batches)):
             r = simulate(pol, arr, slo_ms, args.workers)
             lines.append("%-58s %-9s %8.4f %9.3f %8d" % (name, pol.name, r["slo_attainment"], r["mean_accuracy_rank"], r["dropped"]))
+    # the same policies driving the library on this GPU (one worker): every decision is really run and
+    # the worker is busy for the time the forward took, in virtual time
+    ex = GpuExecutor(net, spec, [C[k] for k in front], batches, make_inputs)
+    for i in range(len(front)):                              # every (cfg, batch) the policies can pick, warmed up
+        for j, b in enumerate(batches):
+            ex(i, j, b)
+    cap1_small = batches[-1] / (table[0, -1] * 1e-3)
+    cap1_large = batches[-1] / (table[-1, -1] * 1e-3)
+    rate1 = 0.6 * float(np.sqrt(cap1_small * cap1_large))
+    lines += ["", "live: one worker = this GPU, every dispatched batch run through sna_subnet_forward and charged the time it took",
+              "capacity at batch 64: %.0f q/s with the smallest subnet, %.0f q/s with the largest" % (cap1_small, cap1_large), "",
+              "%-58s %-9s %8s %9s %8s %9s" % ("trace", "policy", "SLO att.", "acc. rank", "dropped", "forwards")]
+    live = [("bursty, mean %.0f q/s, CV2=%g" % (rate1, cv2), bursty_trace(0.2 * rate1, 0.8 * rate1, cv2, args.live_duration, 300 + k))
+            for k, cv2 in enumerate((2.0, 8.0))]
+    live += [("accelerating %.0f -> %.0f q/s, tau=%.0e q/s2, CV2=8" % (0.3 * cap1_large, 0.6 * cap1_small, 5.0 * cap1_small),
+              accelerating_trace(0.3 * cap1_large, 0.6 * cap1_small, 5.0 * cap1_small, 8.0, args.live_duration, 400))]
+    for name, arr in live:
+        for pol in (SlackFit(table, batches), MaxBatch(table, batches), MaxAcc(table, batches)):
+            ex.calls = 0
+            r = simulate(pol, arr, slo_ms, 1, executor=ex)
+            lines.append("%-58s %-9s %8.4f %9.3f %8d %9d" % (name, pol.name, r["slo_attainment"], r["mean_accuracy_rank"], r["dropped"], ex.calls))
+    net.close()
     report = "\n".join(lines) + "\n"
     print(report)
     if args.out:

@@ -134,3 +134,25 @@ def test_slackfit_trades_accuracy_for_attainment_under_burst():
     rb = {p.name: scheduler.simulate(p, burst, slo_ms=3 * t[-1, -1], n_workers=1)
           for p in (scheduler.SlackFit(t, BATCHES), scheduler.MaxAcc(t, BATCHES))}
     assert rb["SlackFit"]["slo_attainment"] >= rb["MaxAcc"]["slo_attainment"]
+
+
+def test_simulate_charges_what_the_executor_reports():
+    """With an executor the worker is busy for the returned time, not the table's; decisions still come from the table."""
+    table = np.array([[1.0, 2.0], [3.0, 5.0]])
+    pol = scheduler.MaxBatch(table, (1, 2))
+    arrivals = np.array([0.0, 0.0, 0.0, 0.0])
+    calls = []
+
+    def slow(i, j, take):
+        calls.append((i, j, take))
+        return 10.0 * table[i, j]                       # ten times slower than profiled
+
+    fast = scheduler.simulate(pol, arrivals, slo_ms=8.0, n_workers=1)
+    live = scheduler.simulate(pol, arrivals, slo_ms=8.0, n_workers=1, executor=slow)
+    # by hand: slack 8 -> batch 2 of the larger subnet (5 ms), done at 5; slack 3 -> batch 2 of the smaller (2 ms), done at 7
+    assert fast["slo_attainment"] == 1.0
+    assert calls[0] == (1, 1, 2)
+    # ten times slower: the first batch ends at 50 ms, past its deadline; the other two are late at the head and dropped
+    assert live["slo_attainment"] == 0.0 and live["dropped"] == 2
+    assert live["slo_attainment"] < fast["slo_attainment"]
+    assert live["decisions"][0][2:] == fast["decisions"][0][2:]
