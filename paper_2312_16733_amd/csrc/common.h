@@ -123,7 +123,7 @@ struct AttnGroupArgs { int n; AttnProblem p[SNA_MAX_GROUPS]; };
 
 // fused ResNet stem (7x7 stride-2 conv, SubnetNorm, ReLU, 3x3 stride-2 max pool)
 struct StemPoolProblem {
-  const void* x;        // [N][H][W][8] channel-padded request images
+  const void* x;        // request images: [N][H][W][8] channel-padded copy, or the caller's [N][H][W][3] (see pix_b)
   const void* w;        // stem weights stored with 8 input channels, first tap of the 7x7 window
   const float* scale; const float* shift;
   void* y;              // [N][Po][Qo][K]
@@ -133,6 +133,7 @@ struct StemPoolProblem {
   int K;                // active out channels (multiple of 8, <= 64)
   int wk, wr, ws;       // element strides of the stored weight tensor
   unsigned x_bytes;
+  int pix_b;            // bytes between input pixels: 16 for the padded copy, 6 for a 3-channel image read in place
   int tiles_x, tiles_y; // pooled 4 x 16 tiles per image
   int tile_start, tiles;
 };

@@ -574,6 +574,13 @@ struct Fwd {
     }
   }
 
+  // ResNet family: 7x7 stem conv + SubnetNorm + ReLU + max pool as one kernel (which also reads unpadded images)
+  bool resnet_fused_stem() const {
+    const sna_arch_desc& a = T().arch;
+    bool fused = a.dtype == SNA_DTYPE_BF16 && a.in_ch == 3 && tensor("stem.w").dims[1] == 7 && tensor("stem.w").dims[2] == 7;
+    for (const Group& g : groups) fused = fused && g.cfg->stage_out_ch[0] <= 64;
+    return fused && !net->calibrating;     // calibration needs the stem's bare output
+  }
   sna_status run_tiny(const void* inputs, float* logits);
   sna_status run_resnet(const void* inputs, float* logits);
   sna_status run_mbv3(const void* inputs, float* logits);
@@ -600,10 +607,15 @@ struct Fwd {
 
   // bf16 image families: every group's requests are copied into its input buffer with the
   // channels padded to 8 (which also gathers scattered requests), so the stem runs on MFMA.
-  void pad_inputs(const void* inputs, const std::vector<size_t>& req_off) {
+  void pad_inputs(const void* inputs, const std::vector<size_t>& req_off, bool raw_ok) {
     const int c_in = T().arch.in_ch;
     std::vector<PadItem> items;
     for (Group& g : groups) {
+      if (raw_ok && g.contiguous) {        // the first layer reads the caller's images in place
+        g.cur = (const char*)inputs + req_off[g.reqs[0]];
+        g.raw_input = true;
+        continue;
+      }
       const size_t pix = (size_t)g.cfg->in_h * g.cfg->in_w;
       size_t d = (size_t)(g.inbuf - net->arena);
       if (g.contiguous) {
@@ -693,9 +705,7 @@ sna_status Fwd::run_tiny(const void*, float* logits) {
 sna_status Fwd::run_resnet(const void*, float* logits) {
   const sna_arch_desc& a = T().arch;
   for (Group& g : groups) { g.H = g.cfg->in_h; g.W = g.cfg->in_w; g.C = 8; }     // channel-padded inputs
-  bool fused_stem = a.dtype == SNA_DTYPE_BF16 && tensor("stem.w").dims[1] == 7 && tensor("stem.w").dims[2] == 7;
-  for (const Group& g : groups) fused_stem = fused_stem && g.cfg->stage_out_ch[0] <= 64;
-  fused_stem = fused_stem && !net->calibrating;          // calibration needs the stem's bare output
+  const bool fused_stem = resnet_fused_stem();
   if (fused_stem) {
     // stem conv + SubnetNorm + ReLU + max pool in one kernel: the conv output stays in LDS
     StemPoolArgs sa;
@@ -713,7 +723,9 @@ sna_status Fwd::run_resnet(const void*, float* logits) {
       p.scale = scale_of("stem.sn", g.cfg->subnet_id); p.shift = shift_of("stem.sn", g.cfg->subnet_id);
       p.N = g.n; p.H = g.H; p.W = g.W; p.Ho = c.Ho; p.Wo = c.Wo;
       p.Po = out_size(c.Ho, 3, 2); p.Qo = out_size(c.Wo, 3, 2);
-      p.K = c.K; p.wk = c.wk; p.wr = c.wr; p.ws = c.ws; p.x_bytes = c.x_bytes;
+      p.K = c.K; p.wk = c.wk; p.wr = c.wr; p.ws = c.ws;
+      p.pix_b = g.raw_input ? 2 * a.in_ch : 16;
+      p.x_bytes = (unsigned)((size_t)g.n * g.H * g.W * p.pix_b);
       p.tiles_x = (p.Qo + 15) / 16; p.tiles_y = (p.Po + 3) / 4;
       p.tiles = p.N * p.tiles_x * p.tiles_y;
       p.tile_start = start;
@@ -1395,7 +1407,8 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   }
   if ((size_t)(cur - net->arena) > net->arena_bytes) return fail(SNA_E_WORKSPACE, "arena overflow");
 
-  if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3) f.pad_inputs(inputs_dev, req_off);
+  if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3)
+    f.pad_inputs(inputs_dev, req_off, a.family == SNA_FAMILY_RESNET && f.resnet_fused_stem());
   else f.bind_inputs(inputs_dev, req_off, req_bytes);
   sna_status st;
   switch (a.family) {

@@ -41,6 +41,7 @@ struct Group {
   int n = 0;                         // requests routed to this cfg
   std::vector<int> reqs;             // their positions in the call, ascending
   bool contiguous = true;
+  bool raw_input = false;            // cur points at the caller's unpadded request images
   char* buf[NBUF] = {nullptr};
   char* inbuf = nullptr;
   float* small = nullptr;

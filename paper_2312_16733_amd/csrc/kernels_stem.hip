@@ -1,4 +1,5 @@
-// ResNet stem in one kernel: 7x7 stride-2 WeightSlice conv over the channel-padded request image,
+// ResNet stem in one kernel: 7x7 stride-2 WeightSlice conv over the request image (read in place, or a
+// channel-padded copy of scattered requests),
 // SubnetNorm scale/shift, ReLU and the 3x3 stride-2 max pool that follows it.  (WeightSlice and
 // SubnetNorm operators of the paper's section "SubNetAct: Instantaneous Model Actuation": the block
 // reads the leading K_active output channels of the resident 7x7 stem tensor in place and applies the
@@ -63,7 +64,6 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
-  constexpr unsigned OOB = 0x80000000u;
 
   // this lane's conv pixels (one per row tile it computes) and their first input pixel in the patch
   int pbase[3];
@@ -85,8 +85,11 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     lane_yx[pass] = i < NIP ? (iy << 16) | ix : -1;
   }
 
-  // Request the input patch of a tile: global -> LDS, 16 bytes per lane, zeros outside the image.
-  auto request_patch = [&](int t) {
+  // The input patch of a tile goes through registers: three channel loads per pixel at the image's own
+  // pixel stride (so a 3-channel request image is read in place, no padded copy), zeros outside the
+  // image; store_patch() then writes 16 bytes per pixel (channels 3..7 zero) where the MFMAs expect them.
+  unsigned pk[PASSES][2];
+  auto load_patch = [&](int t) {
     const int gp = find_problem(args, t);
     const StemPoolProblem& q = args.p[gp];
     const int local = t - q.tile_start;
@@ -95,18 +98,28 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     const int rem = local - n * per_img;
     const int ty = rem / q.tiles_x, tx = rem - ty * q.tiles_x;
     const int iy0 = 2 * (2 * ty * PH - 1) - 3, ix0 = 2 * (2 * tx * PW - 1) - 3;      // first input pixel of the patch
-    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)q.x, 0, (int)q.x_bytes, 0x00020000);
+    const char* const img = (const char*)q.x;
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
       const int gy = iy0 + (lane_yx[pass] >> 16), gx = ix0 + (lane_yx[pass] & 0xffff);
       const bool ok = lane_yx[pass] >= 0 && gy >= 0 && gy < q.H && gx >= 0 && gx < q.W;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_char*)patch + (pass * 256 + wave * 64) * 16, 16,
-                                               ok ? (unsigned)(((n * q.H + gy) * q.W + gx) * 16) : OOB, 0, 0, 0);
+      unsigned c0 = 0, c1 = 0, c2 = 0;
+      if (ok) {
+        const unsigned short* px = (const unsigned short*)(img + ((long)(n * q.H + gy) * q.W + gx) * q.pix_b);
+        c0 = px[0]; c1 = px[1]; c2 = px[2];
+      }
+      pk[pass][0] = c0 | (c1 << 16);
+      pk[pass][1] = c2;
     }
+  };
+  auto store_patch = [&]() {
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass)
+      *(uint4*)(patch + (pass * 256 + tid) * 16) = make_uint4(pk[pass][0], pk[pass][1], 0u, 0u);
   };
 
   int cur_g = -1;
-  if ((int)blockIdx.x < args.total_tiles) request_patch(blockIdx.x);
+  if ((int)blockIdx.x < args.total_tiles) { load_patch(blockIdx.x); store_patch(); }
   for (int tile = blockIdx.x; tile < args.total_tiles; tile += gridDim.x) {
     const int g = find_problem(args, tile);
     const StemPoolProblem& p = args.p[g];
@@ -137,7 +150,6 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     const int py0 = ty * PH, px0 = tx * PW;
     const int sy0 = 2 * py0 - 1, sx0 = 2 * px0 - 1;          // first conv pixel of the tile (may be -1)
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's part of the patch landed
     __syncthreads();                                         // patch, weights, scale / shift visible to all
 
     // ---- MFMAs out of LDS ---------------------------------------------------------------------
@@ -177,7 +189,8 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     }
 
     __syncthreads();                                         // every wave is done with the patch
-    if (tile + (int)gridDim.x < args.total_tiles) request_patch(tile + gridDim.x);   // lands under the epilogue and the pool
+    const bool more = tile + (int)gridDim.x < args.total_tiles;
+    if (more) load_patch(tile + gridDim.x);                  // arrives under the epilogue and the pool
 
     // ---- SubnetNorm + ReLU, conv tile -> LDS as bf16 ------------------------------------------
     float4 sc[TNJ][4], sh[TNJ][4];
@@ -241,7 +254,8 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
       o.z = __builtin_bit_cast(unsigned, best[2]); o.w = __builtin_bit_cast(unsigned, best[3]);
       *(uint4*)((bf16_t*)p.y + (((long)n * p.Po + py) * p.Qo + px) * K + oct * 8) = o;
     }
-    __syncthreads();                                         // sout and w_lds free for the next tile
+    if (more) store_patch();                                 // the patch region has been free since the barrier after the MFMAs
+    __syncthreads();                                         // sout and w_lds free for the next tile, its patch in place
   }
 #endif
 }
@@ -251,7 +265,8 @@ hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s) {
   for (int i = 0; i < a.n; ++i) {
     const StemPoolProblem& p = a.p[i];
     if (p.K < 8 || p.K > stem::KMAX || p.K % 8 || p.tiles_x * stem::PW < p.Qo || p.tiles_y * stem::PH < p.Po ||
-        p.tiles != p.N * p.tiles_x * p.tiles_y)
+        p.tiles != p.N * p.tiles_x * p.tiles_y || p.pix_b < 6 || p.pix_b % 2 ||
+        (size_t)p.N * p.H * p.W * p.pix_b > (size_t)p.x_bytes)
       return hipErrorInvalidValue;
   }
   bool two = false;
