@@ -98,16 +98,20 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     const int rem = local - n * per_img;
     const int ty = rem / q.tiles_x, tx = rem - ty * q.tiles_x;
     const int iy0 = 2 * (2 * ty * PH - 1) - 3, ix0 = 2 * (2 * tx * PW - 1) - 3;      // first input pixel of the patch
-    const char* const img = (const char*)q.x;
+    // bounds-checked 2-byte loads at 32-bit offsets: a pixel outside the image gets an out-of-range
+    // offset, which reads as zero (the padding)
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)q.x, 0, (int)q.x_bytes, 0x00020000);
+    const int row_b = q.W * q.pix_b;
+    const int base = (n * q.H + iy0) * row_b + ix0 * q.pix_b;       // may be negative; only used where ok
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
-      const int gy = iy0 + (lane_yx[pass] >> 16), gx = ix0 + (lane_yx[pass] & 0xffff);
+      const int ly = lane_yx[pass] >> 16, lx = lane_yx[pass] & 0xffff;
+      const int gy = iy0 + ly, gx = ix0 + lx;
       const bool ok = lane_yx[pass] >= 0 && gy >= 0 && gy < q.H && gx >= 0 && gx < q.W;
-      unsigned c0 = 0, c1 = 0, c2 = 0;
-      if (ok) {
-        const unsigned short* px = (const unsigned short*)(img + ((long)(n * q.H + gy) * q.W + gx) * q.pix_b);
-        c0 = px[0]; c1 = px[1]; c2 = px[2];
-      }
+      const int off = ok ? base + ly * row_b + lx * q.pix_b : (int)0x80000000;
+      const unsigned c0 = __builtin_amdgcn_raw_buffer_load_b16(rsrc_x, off, 0, 0);
+      const unsigned c1 = __builtin_amdgcn_raw_buffer_load_b16(rsrc_x, off + 2, 0, 0);
+      const unsigned c2 = __builtin_amdgcn_raw_buffer_load_b16(rsrc_x, off + 4, 0, 0);
       pk[pass][0] = c0 | (c1 << 16);
       pk[pass][1] = c2;
     }
@@ -266,7 +270,7 @@ hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s) {
     const StemPoolProblem& p = a.p[i];
     if (p.K < 8 || p.K > stem::KMAX || p.K % 8 || p.tiles_x * stem::PW < p.Qo || p.tiles_y * stem::PH < p.Po ||
         p.tiles != p.N * p.tiles_x * p.tiles_y || p.pix_b < 6 || p.pix_b % 2 ||
-        (size_t)p.N * p.H * p.W * p.pix_b > (size_t)p.x_bytes)
+        (size_t)p.N * p.H * p.W * p.pix_b > (size_t)p.x_bytes || p.x_bytes >= 0x80000000u)    // 32-bit offsets; 2^31 marks "outside"
       return hipErrorInvalidValue;
   }
   bool two = false;
