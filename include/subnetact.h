@@ -226,8 +226,8 @@ sna_status sna_subnet_tune(sna_supernet* net,
  * rows and the layers of skipped blocks are left alone), refreshes the folded
  * scale / shift kept in the workspace, and normalises with the values as stored,
  * so that a later sna_subnet_forward of the same cfg on the same inputs returns
- * the same logits (to summation order of the squeeze-excite pool where a family
- * has one).  stats_dev must be the device table given to
+ * the same logits (to summation order where the calibration pass runs a layer
+ * on another kernel than serving does: the squeeze-excite pool, the 7x7 stem).  stats_dev must be the device table given to
  * sna_supernet_load (the caller still owns it; this is the one call that writes
  * it).  logits_dev [n_requests][n_classes] receives that forward's logits.
  * The fp32 outputs of the layers launched together (a block's last convolution

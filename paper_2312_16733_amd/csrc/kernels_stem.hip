@@ -13,12 +13,17 @@
 //
 // Geometry of one tile: PH x PW = 4 x 16 pooled pixels <- (2 PH + 1) x (2 PW + 1) = 9 x 33 conv
 // pixels (the pool's window with its halo; a neighbouring tile recomputes the shared row / column,
-// 16 % extra MFMA work) <- 23 x 71 input pixels of 8 channels (16 bytes) each, kept in LDS with the even
-// columns of a row ahead of the odd ones so that the stride-2 fragment reads are conflict-free.
+// 16 % extra MFMA work) <- 23 x 71 input pixels, kept in LDS as 4 channels (8 bytes: 3 + a zero) each.
+// The window of a conv pixel starts at an even column of the patch (stride 2), so a 16-byte unit of
+// LDS is a pair of horizontally adjacent taps: the reduction runs over 7 window rows x 4 column
+// pairs = 28 units of 8 elements (the eighth column has zero weights), 224 instead of the 392 that
+// one tap per unit with channels padded to 8 would take.
 // MFMA shape: rows = conv pixels of the tile in raster order (297, ten 32-row tiles over 4 waves),
-// columns = output channels (<= 64), reduction = 50 tap slots x 8 channels (49 taps + one zero slot).
+// columns = output channels (<= 64), reduction = 28 units x 8 elements, two units per MFMA.
 // Blocks are persistent: weights, scale and shift go to LDS once per problem, then the block walks
 // its tiles; the next tile's patch is requested as soon as the MFMAs are done with the current one.
+// The conv tile is staged over the patch (free by then), which keeps a block at 76 KB of LDS: two
+// blocks per CU, so one block's MFMAs run under the other's epilogue and pool.
 #include "common.h"
 
 namespace sna {
@@ -29,31 +34,32 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) char lds_char;
 
 namespace stem {
-constexpr int KS = 7, SLOTS = 50;
-[[maybe_unused]] constexpr int TAPS = KS * KS, NSLICE = SLOTS / 2;     // device code only
+constexpr int KS = 7, PAIRS = 4, SLOTS = KS * PAIRS;                    // units of the reduction: (window row, column pair)
+[[maybe_unused]] constexpr int NSLICE = SLOTS / 2;                     // device code only
 constexpr int PH = 4, PW = 16;
 constexpr int SH = 2 * PH + 1, SW = 2 * PW + 1, NSP = SH * SW;          // conv pixels per tile: 9 x 33 = 297
 constexpr int IH = 2 * SH + 5, IW = 2 * SW + 5, NIP = IH * IW;          // input pixels per tile: 23 x 71 = 1633
 constexpr int ROW_TILES = (NSP + 31) / 32;                              // 10
-constexpr int PASSES = (NIP + 255) / 256;                               // 7 DMA passes of 256 pixels
+constexpr int IWP = (IW + 1) / 2;                                       // 36 column pairs per patch row
+constexpr int NIS = IH * IWP * 2;                                       // pixel slots of a patch incl. the spare last column: 1656
+constexpr int PASSES = (NIS + 255) / 256;                               // 7 passes of 256 pixels
 constexpr int KMAX = 64;
 constexpr int W_ROW_B = SLOTS * 16 + 16;                                // one out channel's taps in LDS; the pad spreads rows over banks
 constexpr int OFF_W = 0;
-constexpr int OFF_PATCH = OFF_W + KMAX * W_ROW_B;                       // 51200
-constexpr int OFF_SOUT = OFF_PATCH + PASSES * 256 * 16;                 // + 28672
+constexpr int OFF_PATCH = OFF_W + KMAX * W_ROW_B;                       // 29696
+constexpr int OFF_SOUT = OFF_PATCH;                                     // the conv tile is staged over the patch, free by then
 constexpr int SOUT_ROW_B = KMAX * 2 + 16;                               // one conv pixel: 64 bf16 + pad against bank conflicts
-constexpr int OFF_SS = OFF_SOUT + ROW_TILES * 32 * SOUT_ROW_B;          // + 40960
+constexpr int PATCH_B = PASSES * 256 * 8, SOUT_B = ROW_TILES * 32 * SOUT_ROW_B;
+constexpr int OFF_SS = OFF_PATCH + (PATCH_B > SOUT_B ? PATCH_B : SOUT_B);   // + 46080
 constexpr int SMEM = OFF_SS + 2 * KMAX * 4;
-constexpr int IWE = (IW + 1) / 2;                                       // even input columns of a patch row come first, then the odd ones
-static_assert(SMEM <= 160 * 1024, "LDS");
-static_assert((SW - 1) + (KS - 1) / 2 < IWE && IWE + (SW - 1) + (KS - 2) / 2 < IW && 2 * (SH - 1) + KS - 1 < IH,
-              "fragment reads stay inside the patch");
+static_assert(2 * SMEM <= 160 * 1024, "two blocks per CU");
+static_assert((SW - 1) + PAIRS - 1 < IWP && 2 * (SH - 1) + KS - 1 < IH, "fragment reads stay inside the patch");
 static_assert((2 * (PH - 1) + 2) * SW + 2 * (PW - 1) + 2 < NSP, "pool windows stay inside the conv tile");
 }  // namespace stem
 
 // TWO: some problem of the launch has more than 32 output channels (second 32-channel column tile).
 template <bool TWO>
-__global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs args) {
+__global__ __launch_bounds__(256, 2) void stem_pool_kernel(const StemPoolArgs args) {
 #if defined(__HIP_DEVICE_COMPILE__)        // the host pass needs the symbol only, not the body
   using namespace stem;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -72,22 +78,21 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     const int sp = 32 * (wave + 4 * i) + l32;              // waves 2 and 3 have no third row tile: they redo pixel 0
     const int spc = sp < NSP ? sp : 0;
     const int sy = spc / SW, sx = spc - sy * SW;
-    pbase[i] = ((2 * sy) * IW + sx) * 16;
+    pbase[i] = ((2 * sy) * IWP + sx) * 16;
   }
 
   // which input pixel of a patch each of this thread's DMA lanes fetches (the same for every tile)
   int lane_yx[PASSES];
 #pragma unroll
   for (int pass = 0; pass < PASSES; ++pass) {
-    const int i = pass * 256 + tid;
-    const int iy = i / IW, qq = i - iy * IW;                 // slot qq of a row: even columns, then odd columns
-    const int ix = qq < IWE ? 2 * qq : 2 * (qq - IWE) + 1;
-    lane_yx[pass] = i < NIP ? (iy << 16) | ix : -1;
+    const int i = pass * 256 + tid;                          // pixel slot: row-major, 2 IWP slots per row
+    const int iy = i / (2 * IWP), ix = i - iy * (2 * IWP);
+    lane_yx[pass] = (i < NIS && ix < IW) ? (iy << 16) | ix : -1;     // the spare column past the patch stays zero
   }
 
   // The input patch of a tile goes through registers: three channel loads per pixel at the image's own
   // pixel stride (so a 3-channel request image is read in place, no padded copy), zeros outside the
-  // image; store_patch() then writes 16 bytes per pixel (channels 3..7 zero) where the MFMAs expect them.
+  // image; store_patch() then writes 8 bytes per pixel (3 channels and a zero) where the MFMAs expect them.
   unsigned pk[PASSES][2];
   auto load_patch = [&](int t) {
     const int gp = find_problem(args, t);
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
   auto store_patch = [&]() {
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass)
-      *(uint4*)(patch + (pass * 256 + tid) * 16) = make_uint4(pk[pass][0], pk[pass][1], 0u, 0u);
+      *(uint2*)(patch + (pass * 256 + tid) * 8) = make_uint2(pk[pass][0], pk[pass][1]);
   };
 
   int cur_g = -1;
@@ -132,13 +137,20 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
       // the barrier that ends every tile guarantees that no wave still reads w_lds or ss
       const bf16_t* w = (const bf16_t*)p.w;
       for (int i = tid; i < KMAX * SLOTS; i += 256) {
-        const int k = i / SLOTS, tap = i - k * SLOTS;
+        const int k = i / SLOTS, slot = i - k * SLOTS;
+        const int r = slot / PAIRS, c = 2 * (slot - r * PAIRS);          // taps (r, c) and (r, c + 1), 3 channels each
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (k < K && tap < TAPS) {
-          const int r = tap / KS, c = tap - r * KS;
-          v = *(const uint4*)(w + (long)k * p.wk + (long)r * p.wr + (long)c * p.ws);
+        if (k < K) {
+          const bf16_t* t0 = w + (long)k * p.wk + (long)r * p.wr + (long)c * p.ws;
+          v.x = (unsigned)t0[0] | ((unsigned)t0[1] << 16);
+          v.y = (unsigned)t0[2];
+          if (c + 1 < KS) {
+            const bf16_t* t1 = t0 + p.ws;
+            v.z = (unsigned)t1[0] | ((unsigned)t1[1] << 16);
+            v.w = (unsigned)t1[2];
+          }
         }
-        *(uint4*)(w_lds + k * W_ROW_B + tap * 16) = v;
+        *(uint4*)(w_lds + k * W_ROW_B + slot * 16) = v;
       }
       if (tid < KMAX) {
         ss[tid] = tid < K ? p.scale[tid] : 0.f;
@@ -163,12 +175,11 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
     f32x16 acc[3][TNJ];
     u32x4 af[2][3], bf[2][TNJ];
     auto fetch = [&](int s, int buf) {
-      const int tap = 2 * s + half;                          // slot 49 holds zero weights
-      const int tapc = tap < TAPS ? tap : TAPS - 1;
-      const int r = tapc / KS, c = tapc - r * KS;
-      const int aoff = (r * IW + (c & 1) * IWE + (c >> 1)) * 16;   // stride-2 neighbours sit in adjacent slots
+      const int slot = 2 * s + half;                         // (window row r, column pair jp)
+      const int r = slot / PAIRS, jp = slot - r * PAIRS;
+      const int aoff = (r * IWP + jp) * 16;                  // conv pixel sx, pair jp: patch columns 2 sx + 2 jp, + 1
 #pragma unroll
-      for (int j = 0; j < TNJ; ++j) bf[buf][j] = *(const u32x4*)(w_lds + (32 * j + l32) * W_ROW_B + tap * 16);
+      for (int j = 0; j < TNJ; ++j) bf[buf][j] = *(const u32x4*)(w_lds + (32 * j + l32) * W_ROW_B + slot * 16);
 #pragma unroll
       for (int i = 0; i < 3; ++i) af[buf][i] = *(const u32x4*)(patch + pbase[i] + aoff);
     };
@@ -258,8 +269,9 @@ __global__ __launch_bounds__(256, 1) void stem_pool_kernel(const StemPoolArgs ar
       o.z = __builtin_bit_cast(unsigned, best[2]); o.w = __builtin_bit_cast(unsigned, best[3]);
       *(uint4*)((bf16_t*)p.y + (((long)n * p.Po + py) * p.Qo + px) * K + oct * 8) = o;
     }
-    if (more) store_patch();                                 // the patch region has been free since the barrier after the MFMAs
-    __syncthreads();                                         // sout and w_lds free for the next tile, its patch in place
+    __syncthreads();                                         // every thread is done reading the conv tile, which lies over the patch
+    if (more) store_patch();
+    __syncthreads();                                         // the next tile's patch in place
   }
 #endif
 }
@@ -282,7 +294,7 @@ hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done[two] = true;
   }
-  const int blocks = a.total_tiles < 256 ? a.total_tiles : 256;     // one persistent block per CU
+  const int blocks = a.total_tiles < 512 ? a.total_tiles : 512;     // two persistent blocks per CU
   hipLaunchKernelGGL(fn, dim3(blocks), dim3(256), stem::SMEM, s, a);
   return hipGetLastError();
 }
