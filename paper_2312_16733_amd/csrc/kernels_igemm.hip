@@ -519,7 +519,7 @@ void conv3_slab_kernel(const ConvGroupArgs args) {
 #pragma unroll 1
     for (int it = 0; it < n_it; ++it) {
       const unsigned e = (unsigned)(it * NT + tid);
-      const int px = (int)__umulhi(e, magic), c = (int)e - px * C8p;
+      const int px = C8p == 1 ? (int)e : (int)__umulhi(e, magic), c = (int)e - px * C8p;      // (2^32 / 1 does not fit the magic)
       const int gp = pix0 + px;
       const bool ok = c < C8 && px < P && gp >= 0 && gp < n_pix;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, dst + it * NT * 16, 16, ok ? (unsigned)((gp * C + c * 8) * 2) : OOB,
