@@ -670,27 +670,28 @@ def test_fresh_seeds_small_shapes(torch_mod, k):
         say("  ", name, "worst rel err %.3e" % worst)
 
 
-def test_slab_variants_on_small_odd_images(torch_mod):
-    """The 3x3 kernel that keeps the activation slab in LDS, forced onto every 3x3 stride-1 layer of the small
-    ResNet-shaped SuperNet (images down to 2x2, odd widths, channel counts with even and odd numbers of
-    16-byte units, ragged last tiles, tiles that span several images): same bits as the default choice."""
+def test_all_variants_on_small_odd_images(torch_mod):
+    """Every tile variant, the 3x3 kernel that keeps the activation slab in LDS included, forced onto every
+    layer it can run of the small ResNet- and MBV3-shaped SuperNets (images down to 2x2, odd widths, channel
+    counts of one, even and odd numbers of 16-byte units, ragged last tiles, tiles that span several images):
+    same bits as the default choice."""
     import paper_2312_16733_amd as sna
     torch = torch_mod
-    spec = SMALL_RESNET
-    W, S, C = setup(spec, 8)
-    net = sna.Supernet(spec, W, S, 8, 16)
     nv = sna.lib().sna_tile_variant_count()
-    try:
-        for c in C:
-            for batch in (1, 7):
-                x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 50 + batch)
-                net.set_tile_variant(-1)
-                ref = run_single(torch, net, spec, c, x)
-                for v in range(16, nv):
-                    net.set_tile_variant(v)
-                    got = run_single(torch, net, spec, c, x)
-                    np.testing.assert_array_equal(got, ref, err_msg=f"cfg {c.subnet_id} batch {batch} variant {v}")
-            say("small resnet cfg", c.subnet_id, "res", c.in_h, "slab variants 16..%d: same bits" % (nv - 1))
-    finally:
-        net.set_tile_variant(-1)
-        net.close()
+    for name, spec, n_cfg in (("resnet-small", SMALL_RESNET, 8), ("mbv3-small", synth.MBV3Spec(res_choices=(40, 48, 57)), 6)):
+        W, S, C = setup(spec, n_cfg)
+        net = sna.Supernet(spec, W, S, n_cfg, 16)
+        try:
+            for c in C:
+                for batch in (1, 7):
+                    x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 50 + batch)
+                    net.set_tile_variant(-1)
+                    ref = run_single(torch, net, spec, c, x)
+                    for v in range(nv):
+                        net.set_tile_variant(v)
+                        got = run_single(torch, net, spec, c, x)
+                        np.testing.assert_array_equal(got, ref, err_msg=f"{name} cfg {c.subnet_id} batch {batch} variant {v}")
+                say(name, "cfg", c.subnet_id, "res", c.in_h, "variants 0..%d: same bits" % (nv - 1))
+        finally:
+            net.set_tile_variant(-1)
+            net.close()
