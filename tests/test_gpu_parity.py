@@ -695,3 +695,36 @@ def test_all_variants_on_small_odd_images(torch_mod):
         finally:
             net.set_tile_variant(-1)
             net.close()
+
+
+def test_policies_drive_the_library(torch_mod):
+    """The event loop with a GpuExecutor: every dispatched batch really runs on the resident SuperNet."""
+    import paper_2312_16733_amd as sna
+    from paper_2312_16733_amd import profiler, scheduler
+    torch = torch_mod
+    spec = SMALL_RESNET
+    W, S, C = setup(spec, 8, fixed_res=48)
+    net = sna.Supernet(spec, W, S, 8, 8)
+    try:
+        batches = (1, 2, 4, 8)
+
+        def make_inputs(c, b):
+            return to_dev(torch, spec, synth.make_inputs(spec, b, c.in_h, c.in_w, 9))
+
+        full = profiler.profile_latency(net, spec, C, make_inputs, batches, reps=3, warmup=1)
+        front = profiler.pareto_subset(full)
+        front = [front[k] for k in profiler.pareto_subset(full[front], col=0)]
+        table = full[front]
+        ex = scheduler.GpuExecutor(net, spec, [C[k] for k in front], batches, make_inputs)
+        slo_ms = 20.0 * float(table.max())
+        arrivals = scheduler.bursty_trace(200.0, 800.0, 4.0, 0.05, 11)
+        for pol in (scheduler.SlackFit(table, batches, n_buckets=8), scheduler.MaxBatch(table, batches)):
+            ex.calls = 0
+            r = scheduler.simulate(pol, arrivals, slo_ms, 1, executor=ex)
+            say(pol.name, "attainment", r["slo_attainment"], "forwards", ex.calls, "queries", r["queries"])
+            assert r["queries"] == len(arrivals) and ex.calls == len(r["decisions"]) > 0
+            assert r["served"] + r["dropped"] == r["queries"]
+            assert r["slo_attainment"] > 0.9                   # far below capacity with a generous deadline
+        assert ex.busy_ms > 0
+    finally:
+        net.close()
