@@ -265,7 +265,9 @@ sna_status sna_set_k_split(sna_supernet* net, int32_t mode);
 
 /* Test / timing knob: force every conv / linear launch of the matrix kernel onto tile variant
  * `variant` (0 <= variant < sna_tile_variant_count()), or back to the measured / heuristic choice
- * with -1.  The result does not depend on the variant.  Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
+ * with -1.  A variant that cannot run a layer (some take 3x3 stride-1 convolutions only) leaves that
+ * layer on its usual choice.  The result does not depend on the variant.  Errors: SNA_E_NULL,
+ * SNA_E_CFG_RANGE. */
 int32_t sna_tile_variant_count(void);
 sna_status sna_set_tile_variant(sna_supernet* net, int32_t variant);
 
