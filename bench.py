@@ -1,6 +1,6 @@
 """Benchmark of the SubNetAct forward path on one MI355X.
 
-Workload (BASELINE config 2): the ResNet-50-shaped elastic SuperNet in bf16, 16 seeded subnet
+Workload (benchmark config 2): the ResNet-50-shaped elastic SuperNet in bf16, 16 seeded subnet
 cfgs ordered smallest to largest, batch 64, synthetic inputs resident in HBM.  One step = one
 subnet_forward call over a batch of 64 requests of one cfg; consecutive steps walk the cfg list,
 so K steps sweep the subnet range K/16 times (and actuate a different subnet on every call).
@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--family", default="resnet", choices=["resnet", "mbv3", "transformer"],
-                    help="resnet = the headline workload (BASELINE config 2); the others are extra reports")
+                    help="resnet = the headline workload (benchmark config 2); the others are extra reports")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--save-tuning", action="store_true",
@@ -200,7 +200,7 @@ def main():
                                          "gmacs_per_image": synth.subnet_macs(spec, C[ci]) / 1e9}
 
         if args.family == "resnet":
-            # BASELINE config 4: one call that mixes the cfgs, 64 requests routed Zipf(1.1) over them
+            # benchmark config 4: one call that mixes the cfgs, 64 requests routed Zipf(1.1) over them
             Cm = synth.enumerate_cfgs(spec, n_cfgs, 16733, fixed_res=224)
             routem = synth.zipf_assignment(64, n_cfgs, 4)
             xm = torch.from_numpy(synth.make_inputs(spec, 64, 224, 224, 13)).to(torch.bfloat16).to(dev)
@@ -221,9 +221,9 @@ def main():
            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": {"resnet": "ResNet-50-shaped elastic SuperNet (BASELINE config 2)",
-                                   "mbv3": "MobileNetV3-shaped elastic SuperNet (BASELINE config 3)",
-                                   "transformer": "elastic-width Transformer SuperNet (BASELINE config 5), "
+           "config": {"workload": {"resnet": "ResNet-50-shaped elastic SuperNet (benchmark config 2)",
+                                   "mbv3": "MobileNetV3-shaped elastic SuperNet (benchmark config 3)",
+                                   "transformer": "elastic-width Transformer SuperNet (benchmark config 5), "
                                                   "requests of 128 tokens"}[args.family] +
                                   f", bf16, batch {B}, {n_cfgs} seeded subnet cfgs walked smallest to largest, "
                                   "one cfg per step",
