@@ -1490,7 +1490,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
   const int forced_was = net->forced_variant;
   net->plan_cache_on = false;
   net->prof_on = true;
-  const int nv = igemm_num_variants(), rounds = 3;
+  const int nv = igemm_num_variants(), rounds = 7;
   std::map<std::array<int, 6>, std::vector<std::vector<double>>> samples;   // key -> [variant][round]
   for (int round = 0; round <= rounds && st == SNA_OK; ++round)             // round 0 warms up, not recorded
     for (int v = 0; v < nv && st == SNA_OK; ++v) {
