@@ -88,7 +88,8 @@ void igemm_kernel(const ConvGroupArgs args) {
   static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
   static_assert(BM % 8 == 0 && BN % 8 == 0 && Cfg::PASS_ROWS % 8 == 0, "DMA rows come in groups of 8");
   constexpr int A_IT = Cfg::A_IT, B_IT = Cfg::B_IT, L = A_IT + B_IT;   // DMA loads per thread per stage
-  static_assert((NS - 2) * L < 64, "vmcnt range");
+  static_assert(NS >= 1 && (NS - 2) * L < 64, "vmcnt range");
+  static_assert(NS > 1 || !WS, "a fetching wave needs a second stage to run ahead");
   static_assert(BM % Cfg::PASS_ROWS == 0 && BN % Cfg::PASS_ROWS == 0, "every wave issues the same number of loads");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -313,13 +314,24 @@ void igemm_kernel(const ConvGroupArgs args) {
   int stage = 0, fill = NS - 1;            // stage holding step kt; stage that step kt + NS - 1 goes to
   bool fresh = true;
   for (int kt = 0; kt < KT; ++kt) {
-    // step kt's loads were issued NS-1 steps ago; up to NS-2 newer steps may stay in flight
-    if (do_load) {
-      if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
-      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    if constexpr (NS == 1) {
+      // a single stage: the step is fetched, awaited and consumed in turn.  Nothing overlaps inside the
+      // block; the small LDS footprint lets more blocks share a CU, which is what short reductions need.
+      if (kt > 0) __builtin_amdgcn_s_barrier();            // every wave is done reading the stage
+      if (do_load) {
+        issue(0);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      }
+      __builtin_amdgcn_s_barrier();                        // every wave's part of step kt is in LDS
+    } else {
+      // step kt's loads were issued NS-1 steps ago; up to NS-2 newer steps may stay in flight
+      if (do_load) {
+        if (kt + NS - 1 <= KT) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      }
+      __builtin_amdgcn_s_barrier();          // every wave's part of step kt is in LDS; step kt-1 fully consumed
+      if (do_load && kt + NS - 1 < KT) issue(fill);
     }
-    __builtin_amdgcn_s_barrier();          // every wave's part of step kt is in LDS; step kt-1 fully consumed
-    if (do_load && kt + NS - 1 < KT) issue(fill);
     if (do_math) compute(stage, fresh);
     fresh = false;
     stage = stage + 1 == NS ? 0 : stage + 1;
@@ -920,6 +932,9 @@ static const Variant kVariants[] = {
     // 16..: 3x3 stride-1 layers with the activation slab in LDS
     SNA_SLAB_VARIANT(128, 128, 2, 2, 2), SNA_SLAB_VARIANT(128, 64, 2, 2, 2), SNA_SLAB_VARIANT(128, 96, 4, 1, 2),
     SNA_SLAB_VARIANT(64, 64, 2, 2, 2), SNA_SLAB_VARIANT(64, 128, 1, 4, 2), SNA_SLAB_VARIANT(128, 96, 4, 1, 3),
+    // 22..: one LDS stage, for short reductions: less LDS per block, more blocks per CU
+    SNA_VARIANT(128, 128, 2, 2, 1), SNA_VARIANT(128, 64, 2, 2, 1), SNA_VARIANT(128, 96, 4, 1, 1), SNA_VARIANT(64, 128, 1, 4, 1),
+    SNA_VARIANT(128, 32, 4, 1, 1), SNA_VARIANT(64, 64, 2, 2, 1),
 #ifdef SNA_EXTRA_VARIANTS
     SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
     SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 4),
