@@ -271,6 +271,32 @@ class Supernet:
     def prepare_cfgs(self, cfgs):
         return (SubnetCfgC * len(cfgs))(*[cfg_to_c(c) for c in cfgs])
 
+    def _request_elems(self, cfg_c) -> int:
+        """Input elements one request of this cfg occupies."""
+        if self.spec.family == "transformer":
+            return int(cfg_c.in_h) * self.spec.hidden
+        return int(cfg_c.in_h) * int(cfg_c.in_w) * self.spec.in_ch
+
+    def _check_buffers(self, cfgs_c, req_cfg, inputs, logits, hidden):
+        """The library trusts the caller's buffer sizes; refuse tensors shorter than the routed requests need."""
+        n = len(req_cfg)
+        if n > self.max_batch:
+            return                                      # the library's to report, as are bad indices and cfgs
+        need = 0
+        for r in req_cfg:
+            if not 0 <= int(r) < len(cfgs_c):
+                return
+            c = cfgs_c[int(r)]
+            if not (0 < c.in_h <= self.arch.max_res and 0 < c.in_w <= max(self.arch.max_res, 1)):
+                return
+            need += self._request_elems(c)
+        if inputs.numel() < need:
+            raise ValueError(f"inputs hold {inputs.numel()} elements, the {n} routed requests need {need}")
+        if logits is not None and logits.numel() < n * self.spec.n_classes:
+            raise ValueError(f"logits hold {logits.numel()} elements, need {n * self.spec.n_classes}")
+        if hidden is not None and hidden.numel() < n * self.spec.seq_len * self.spec.hidden:
+            raise ValueError(f"hidden holds {hidden.numel()} elements, need {n * self.spec.seq_len * self.spec.hidden}")
+
     def tune(self, cfgs, req_cfg, inputs, hidden=None, stream=None):
         """One forward that also measures the tile variants of every layer shape it meets."""
         return self.forward(cfgs, req_cfg, inputs, hidden=hidden, stream=stream, tune=True)
@@ -281,9 +307,14 @@ class Supernet:
         torch = self.torch
         cfgs_c = self.prepare_cfgs([cfg])
         assert inputs.dtype == self.act_dtype and inputs.is_contiguous() and inputs.device == self.device
-        n = inputs.shape[0]
+        per = self._request_elems(cfgs_c[0])
+        if per <= 0 or inputs.numel() % per:
+            raise ValueError(f"inputs hold {inputs.numel()} elements, not a whole number of requests of {per}")
+        n = inputs.numel() // per
         if logits is None:
             logits = torch.empty((n, self.spec.n_classes), dtype=torch.float32, device=self.device)
+        elif logits.numel() < n * self.spec.n_classes:
+            raise ValueError(f"logits hold {logits.numel()} elements, need {n * self.spec.n_classes}")
         if stream is None:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         _check(lib().sna_subnet_calibrate(self.handle, cfgs_c, n, inputs.data_ptr(), self.stats.data_ptr(),
@@ -314,6 +345,7 @@ class Supernet:
         cfgs_c = cfgs if isinstance(cfgs, C.Array) else self.prepare_cfgs(cfgs)
         n = len(req_cfg)
         assert inputs.dtype == self.act_dtype and inputs.is_contiguous() and inputs.device == self.device
+        self._check_buffers(cfgs_c, req_cfg, inputs, logits, hidden)
         if logits is None:
             logits = torch.empty((n, self.spec.n_classes), dtype=torch.float32, device=self.device)
         if stream is None:

@@ -100,13 +100,30 @@ def test_resnet_full_supernet(torch_mod, resnet_full, ci, batch):
     say("   rel err %.3e undecided %d" % (e, und))
 
 
+def test_resnet_every_benchmark_cfg(torch_mod, resnet_full):
+    """All 16 benchmark cfgs at full size against the oracle at batch 1, and the smallest, median and
+    largest at batch 16 (every request of the batch)."""
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    worst = 0.0
+    for ci, c in enumerate(C):
+        for batch in ((1, 16) if ci in (0, len(C) // 2, len(C) - 1) else (1,)):
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 60 + batch)
+            say("resnet every-cfg: cfg", ci, "batch", batch, "res", c.in_h)
+            got = run_single(torch, net, spec, c, x)
+            e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"resnet cfg {ci} b{batch}")
+            worst = max(worst, e)
+    say("resnet every-cfg worst rel err %.3e" % worst)
+
+
 def test_resnet_batch64_sampled(torch_mod, resnet_full):
     """Full batch 64 in the benchmark's launch configuration; the oracle checks sampled requests
     one by one (per-request results do not depend on batch mates)."""
     import oracle
     torch = torch_mod
     spec, W, S, C, net = resnet_full
-    for ci in (0, 7, 15):
+    for ci in (0, 7, 11, 15):
         c = C[ci]
         x = synth.make_inputs(spec, 64, c.in_h, c.in_w, 12)
         say("resnet b64 cfg", ci)
@@ -135,7 +152,9 @@ def test_mixed_batch_equals_single_subnet_runs(torch_mod, resnet_full):
         idx = np.nonzero(route == ci)[0]
         single = run_single(torch, net, spec, C[ci], x[idx])
         np.testing.assert_array_equal(got[idx], single, err_msg=f"cfg {ci}")
-    for r in (0, 21, 63):            # and against the oracle on sampled requests
+    # and against the oracle: the first request routed to each distinct cfg, plus the last request
+    for r in sorted({int(np.nonzero(route == ci)[0][0]) for ci in set(route.tolist())} | {63}):
+        say("mixed batch: request", r, "cfg", int(route[r]), "against the oracle")
         check_parity(got[r:r + 1], oracle.forward(spec, W, S, C[route[r]], x[r:r + 1]), "bf16", f"mixed req {r}")
 
 
@@ -246,6 +265,22 @@ def test_mbv3_full_supernet(torch_mod, mbv3_full, ci, batch):
     say("   rel err %.3e undecided %d" % (e, und))
 
 
+def test_mbv3_every_benchmark_cfg(torch_mod, mbv3_full):
+    """All 16 benchmark cfgs at full size at batch 1; smallest, median and largest at batch 16."""
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = mbv3_full
+    worst = 0.0
+    for ci, c in enumerate(C):
+        for batch in ((1, 16) if ci in (0, len(C) // 2, len(C) - 1) else (1,)):
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 70 + batch)
+            say("mbv3 every-cfg: cfg", ci, "batch", batch, "res", c.in_h)
+            got = run_single(torch, net, spec, c, x)
+            e, und = check_parity(got, oracle.forward(spec, W, S, c, x), "bf16", f"mbv3 cfg {ci} b{batch}")
+            worst = max(worst, e)
+    say("mbv3 every-cfg worst rel err %.3e" % worst)
+
+
 def test_mbv3_batch64_sampled_and_mixed(torch_mod, mbv3_full):
     import oracle
     torch = torch_mod
@@ -267,7 +302,7 @@ def test_mbv3_batch64_sampled_and_mixed(torch_mod, mbv3_full):
         idx = np.nonzero(route == ci)[0]
         single = run_single(torch, net, spec, C[ci], np.concatenate([xs[r] for r in idx]))
         np.testing.assert_array_equal(mixed[idx], single, err_msg=f"cfg {ci}")
-    for r in (0, 11, 23):
+    for r in sorted({int(np.nonzero(route == ci)[0][0]) for ci in set(route.tolist())} | {23}):
         check_parity(mixed[r:r + 1], oracle.forward(spec, W, S, C[route[r]], xs[r]), "bf16", f"mbv3 mixed req {r}")
 
 
@@ -305,6 +340,24 @@ def test_transformer_full_supernet(torch_mod, tf_full, ci, batch):
     assert he <= 2e-2
 
 
+def test_transformer_every_benchmark_cfg(torch_mod, tf_full):
+    """All 12 benchmark cfgs at batch 1 (logits and final hidden states); smallest, median, largest at batch 4."""
+    import oracle
+    torch = torch_mod
+    spec, W, S, C, net = tf_full
+    worst = 0.0
+    for ci, c in enumerate(C):
+        for batch in ((1, 4) if ci in (0, len(C) // 2, len(C) - 1) else (1,)):
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 80 + batch)
+            say("transformer every-cfg: cfg", ci, "batch", batch, "depth", c.depth[0])
+            got, hid = run_tf(torch, net, spec, [c], np.zeros(batch, np.int32), x)
+            ref, ref_hid = oracle.forward(spec, W, S, c, x, return_hidden=True)
+            e, und = check_parity(got, ref, "bf16", f"transformer cfg {ci} b{batch}")
+            assert np.abs(hid - ref_hid).max() <= 2e-2 * np.abs(ref_hid).max(), f"hidden states cfg {ci}"
+            worst = max(worst, e)
+    say("transformer every-cfg worst rel err %.3e" % worst)
+
+
 def test_transformer_batch32_sampled_and_mixed(torch_mod, tf_full):
     import oracle
     torch = torch_mod
@@ -323,7 +376,7 @@ def test_transformer_batch32_sampled_and_mixed(torch_mod, tf_full):
         single, shid = run_tf(torch, net, spec, [C[ci]], np.zeros(len(idx), np.int32), x[idx])
         np.testing.assert_array_equal(mixed[idx], single, err_msg=f"cfg {ci}")
         np.testing.assert_array_equal(mhid[idx], shid, err_msg=f"cfg {ci} hidden")
-    for r in (3, 30):
+    for r in sorted({int(np.nonzero(route == ci)[0][0]) for ci in set(route.tolist())} | {30}):
         check_parity(mixed[r:r + 1], oracle.forward(spec, W, S, C[route[r]], x[r:r + 1]), "bf16", f"tf mixed req {r}")
 
 
@@ -503,6 +556,55 @@ def test_replayed_launch_list_follows_the_callers_buffers(torch_mod, resnet_full
     np.testing.assert_array_equal(m1, m1b)
     np.testing.assert_array_equal(m1[0], m2[0])
     assert not np.array_equal(m1[1], m2[1])
+
+
+def test_replayed_launch_list_other_families(torch_mod, mbv3_full, tf_full):
+    """Replay of a recorded launch list on the MBV3- and transformer-shaped families: other input and
+    output buffers on the second call, hidden states wanted or not."""
+    torch = torch_mod
+    spec, W, S, C, net = mbv3_full
+    c = C[6]
+    r = np.zeros(3, np.int32)
+    xa = to_dev(torch, spec, synth.make_inputs(spec, 3, c.in_h, c.in_w, 91))
+    xb = to_dev(torch, spec, synth.make_inputs(spec, 3, c.in_h, c.in_w, 92))
+    la = net.forward([c], r, xa).cpu().numpy()
+    lb = net.forward([c], r, xb).cpu().numpy()          # replay on another input buffer
+    out = torch.zeros((3, spec.n_classes), dtype=torch.float32, device="cuda:0")
+    net.forward([c], r, xa, logits=out)                 # replay into another logits buffer
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), la)
+    assert not np.array_equal(la, lb)
+    net.set_tile_variant(-1)                            # drops the recorded lists: a fresh list must agree
+    np.testing.assert_array_equal(net.forward([c], r, xb).cpu().numpy(), lb)
+    spec, W, S, C, net = tf_full
+    c = C[4]
+    r = np.zeros(2, np.int32)
+    xa, xb = synth.make_inputs(spec, 2, c.in_h, c.in_w, 93), synth.make_inputs(spec, 2, c.in_h, c.in_w, 94)
+    a1 = run_tf(torch, net, spec, [c], r, xa)
+    b1 = run_tf(torch, net, spec, [c], r, xb)           # replay: new inputs, new hidden buffer
+    a2 = run_tf(torch, net, spec, [c], r, xa)
+    np.testing.assert_array_equal(a1[0], a2[0]); np.testing.assert_array_equal(a1[1], a2[1])
+    assert not np.array_equal(a1[0], b1[0])
+    nohid = net.forward([c], r, to_dev(torch, spec, xb)).cpu().numpy()      # other key: no hidden states
+    np.testing.assert_array_equal(nohid, b1[0])
+    net.set_tile_variant(-1)
+    b2 = run_tf(torch, net, spec, [c], r, xb)
+    np.testing.assert_array_equal(b1[0], b2[0]); np.testing.assert_array_equal(b1[1], b2[1])
+
+
+def test_binding_rejects_short_buffers(torch_mod, resnet_full):
+    """A tensor shorter than the routed requests need must never reach the kernels."""
+    torch = torch_mod
+    spec, W, S, C, net = resnet_full
+    c = C[2]
+    x = to_dev(torch, spec, synth.make_inputs(spec, 2, c.in_h, c.in_w, 95))
+    with pytest.raises(ValueError):
+        net.forward([c], [0, 0, 0], x)                  # three requests, two images
+    small = torch.zeros((1, spec.n_classes), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(ValueError):
+        net.forward([c], [0, 0], x, logits=small)
+    with pytest.raises(ValueError):
+        net.calibrate(c, x.flatten()[:-8].reshape(-1))
 
 
 def test_tuning_table_round_trip_and_rejects_bad_lines(torch_mod):
