@@ -22,7 +22,10 @@
  *     repacks weights per subnet.
  *   - All functions return SNA_OK (0) or a negative sna_status; the text of the
  *     last error on the calling thread is available from sna_last_error().
- *     On error nothing has been launched and the handle stays usable.
+ *     Argument and cfg validation comes first: a validation error (every status
+ *     except SNA_E_HIP) means nothing has been enqueued.  SNA_E_HIP reports a
+ *     failed HIP call, possibly in the middle of the launch list: outputs may
+ *     then be partly written.  The handle stays usable either way.
  *   - Activations are NHWC, channel-fastest, densely packed.
  */
 #ifndef SUBNETACT_H
@@ -187,7 +190,8 @@ sna_status sna_supernet_load(const sna_arch_desc* arch,
  *   hidden_dev     TRANSFORMER only, may be NULL: final hidden states
  *                  [n_requests][seq][hidden] in the architecture's dtype
  *   hip_stream     hipStream_t; everything is enqueued on it, no host sync
- * Validation happens on the host first; on error nothing is enqueued.
+ * Validation happens on the host first; on a validation error nothing is enqueued
+ * (see the conventions above for SNA_E_HIP).
  * Calls on one handle must not overlap (they share the workspace).
  */
 sna_status sna_subnet_forward(sna_supernet* net,
@@ -195,6 +199,36 @@ sna_status sna_subnet_forward(sna_supernet* net,
                               const int32_t* req_cfg, int32_t n_requests,
                               const void* inputs_dev, float* logits_dev,
                               void* hidden_dev, void* hip_stream);
+
+/*
+ * sna_subnet_forward for callers that cannot allocate device memory or hand over a
+ * large workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels, same bits in the results.
+ * The per-call scratch (activation buffers, request gather, pooled vectors, fp32
+ * partial sums of split reductions) is taken from a static device array inside the
+ * library instead of the handle's workspace; only the folded SubnetNorm tables
+ * written by sna_supernet_load are still read from the workspace.  The array holds
+ * sna_static_scratch_bytes() = 256 MiB per GPU, from library load until the process
+ * ends: 224 MiB for activations, sized like the workspace (per request, at the
+ * architecture's max_res), which is 8 requests of a ResNet-50-shaped SuperNet with
+ * max_res 224, 11 of the MBV3-shaped one, 36 128-token requests of the 12 x 768
+ * transformer; 32 MiB for split-reduction partial sums (a layer whose partial sums
+ * do not fit is reduced inside its blocks instead: same bits).  A call whose requests need more returns
+ * SNA_E_WORKSPACE with the sizes in sna_last_error(), before anything is enqueued.
+ * Makes no hipMalloc / hipFree and calls no allocating library routine; the array's
+ * device address is resolved once per device (by sna_supernet_load on that device,
+ * else by the first call).  Nothing in the array needs a defined initial value, and
+ * nothing is kept in it between calls.  All calls on one GPU share the one array:
+ * calls that overlap in time on a GPU (two streams, two handles, two threads) race;
+ * serialise them.  Not available while sna_profile_enable is on (SNA_E_BATCH).
+ * Other errors: as sna_subnet_forward.
+ */
+sna_status sna_subnet_forward_static(sna_supernet* net,
+                                     const sna_subnet_cfg* cfgs, int32_t n_cfgs,
+                                     const int32_t* req_cfg, int32_t n_requests,
+                                     const void* inputs_dev, float* logits_dev,
+                                     void* hidden_dev, void* hip_stream);
+int64_t sna_static_scratch_bytes(void);
 
 /* Same arguments and result as sna_subnet_forward, but every conv / linear layer
  * shape met for the first time on this handle gets a measured tile variant of the

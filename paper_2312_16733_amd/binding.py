@@ -83,6 +83,8 @@ def lib():
     L.sna_subnet_forward.argtypes = [vp, C.POINTER(SubnetCfgC), i32, C.POINTER(i32), i32, vp, vp, vp, vp]
     L.sna_subnet_forward.restype = i32
     L.sna_subnet_tune.argtypes = L.sna_subnet_forward.argtypes; L.sna_subnet_tune.restype = i32
+    L.sna_subnet_forward_static.argtypes = L.sna_subnet_forward.argtypes; L.sna_subnet_forward_static.restype = i32
+    L.sna_static_scratch_bytes.argtypes = []; L.sna_static_scratch_bytes.restype = i64
     L.sna_subnet_calibrate.argtypes = [vp, vp, i32, vp, vp, vp, vp]; L.sna_subnet_calibrate.restype = i32
     L.sna_tuned_count.argtypes = [vp]; L.sna_tuned_count.restype = i32
     L.sna_tuning_export.argtypes = [vp, C.c_char_p, i64]; L.sna_tuning_export.restype = i64
@@ -224,11 +226,11 @@ def supernet_load(arch, weights_dev_ptr, weights_bytes, stats_dev_ptr, stats_byt
 
 
 def subnet_forward(handle, cfgs_c, req_cfg, inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr=None, stream=0,
-                   tune=False):
+                   tune=False, static=False):
     n_cfgs = len(cfgs_c)
     arr = cfgs_c if isinstance(cfgs_c, C.Array) else (SubnetCfgC * n_cfgs)(*cfgs_c)
     rc = np.ascontiguousarray(req_cfg, dtype=np.int32)
-    fn = lib().sna_subnet_tune if tune else lib().sna_subnet_forward
+    fn = lib().sna_subnet_tune if tune else (lib().sna_subnet_forward_static if static else lib().sna_subnet_forward)
     _check(fn(handle, arr, n_cfgs, rc.ctypes.data_as(C.POINTER(C.c_int32)),
               len(rc), inputs_dev_ptr, logits_dev_ptr, hidden_dev_ptr, stream))
 
@@ -339,8 +341,9 @@ class Supernet:
         b = text.encode()
         _check(lib().sna_tuning_import(self.handle, b, len(b)))
 
-    def forward(self, cfgs, req_cfg, inputs, logits=None, hidden=None, stream=None, tune=False):
-        """inputs: device tensor of the architecture's dtype, requests concatenated (flat is fine)."""
+    def forward(self, cfgs, req_cfg, inputs, logits=None, hidden=None, stream=None, tune=False, static=False):
+        """inputs: device tensor of the architecture's dtype, requests concatenated (flat is fine).
+        static=True calls sna_subnet_forward_static (pass `logits` too if the caller must not allocate)."""
         torch = self.torch
         cfgs_c = cfgs if isinstance(cfgs, C.Array) else self.prepare_cfgs(cfgs)
         n = len(req_cfg)
@@ -351,7 +354,7 @@ class Supernet:
         if stream is None:
             stream = torch.cuda.current_stream(self.device).cuda_stream
         subnet_forward(self.handle, cfgs_c, req_cfg, inputs.data_ptr(), logits.data_ptr(),
-                       hidden.data_ptr() if hidden is not None else None, stream, tune=tune)
+                       hidden.data_ptr() if hidden is not None else None, stream, tune=tune, static=static)
         return logits
 
     def last_forward_info(self):

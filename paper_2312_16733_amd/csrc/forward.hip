@@ -5,6 +5,8 @@
 #include <cstdio>
 #include <cstring>
 #include <functional>
+#include <memory>
+#include <mutex>
 #include <set>
 
 #include "host.h"
@@ -256,7 +258,7 @@ struct Fwd {
     for (size_t i = 0; i < n; ++i) {
       ConvProblem& q = ps[i];
       const size_t part_bytes = align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
-      const bool can_split = chunks[i] > 1 && (size_t)(part_cur - net->partials) + part_bytes <= kPartialBytes;
+      const bool can_split = chunks[i] > 1 && (size_t)(part_cur - net->partials) + part_bytes <= net->partials_bytes;
       ConvProblem r = q, qs = q;         // the reduction finishes the layer: keeps y, norm, residual, activation
       if (can_split) {
         r.x = part_cur;
@@ -414,7 +416,7 @@ struct Fwd {
   bool cal_scratch(char*& cur, int M, int K, float*& raw, float*& part) {
     const size_t raw_b = align_up((size_t)M * K * 4, 256);
     const size_t part_b = align_up((size_t)((M + SNA_CAL_ROWS - 1) / SNA_CAL_ROWS) * K * 3 * 4, 256);
-    if ((size_t)(cur - net->partials) + raw_b + part_b > kPartialBytes) { err = hipErrorOutOfMemory; return false; }
+    if ((size_t)(cur - net->partials) + raw_b + part_b > net->partials_bytes) { err = hipErrorOutOfMemory; return false; }
     raw = (float*)cur; part = (float*)(cur + raw_b);
     cur += raw_b + part_b;
     return true;
@@ -1225,6 +1227,45 @@ static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t 
 
 constexpr size_t kMaxPlans = 64;
 
+// ---- static device scratch for the entry point that allocates nothing ---------------------------
+// The per-call scratch of a forward (activation arena, input gather, small fp32 vectors, fp32 partial
+// sums of split reductions) normally lives in the workspace the caller allocated.  Callers that cannot
+// allocate get it from this array instead.  Each GPU holds its own copy at its own address, resolved
+// once per device; host code only ever uses the resolved pointer.
+constexpr size_t kStaticScratchBytes = (size_t)256 << 20;
+constexpr size_t kStaticPartialBytes = (size_t)32 << 20;      // tail of the array: split-reduction partial sums
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (resolved on first use there), or nullptr with the
+// error text set.
+static char* static_scratch_base() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(SNA_E_HIP, "hipGetDevice: %s", e != hipSuccess ? hipGetErrorString(e) : "device index out of range");
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fail(SNA_E_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+static sna_status forward_impl(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs, const int32_t* req_cfg,
+                               int32_t n_requests, const void* inputs_dev, float* logits_dev, void* hidden_dev,
+                               void* hip_stream, bool static_scratch);
+
 extern "C" {
 
 const char* sna_last_error(void) { return last_error_text(); }
@@ -1311,8 +1352,12 @@ sna_status sna_supernet_load(const sna_arch_desc* arch, const void* weights_dev,
   net->arena = net->workspace + folded_bytes(net->T, n_subnets);
   net->arena_bytes = workspace_bytes - folded_bytes(net->T, n_subnets) - kPartialBytes;
   net->partials = net->arena + net->arena_bytes / 256 * 256;
+  net->partials_bytes = kPartialBytes;
   net->n_subnets = n_subnets;
   net->max_batch = max_batch;
+  // resolve this device's static scratch now, outside any stream capture a later forward may run under
+  // (a failure here is reported by the entry point that needs it)
+  (void)static_scratch_base();
   hipError_t e = launch_fold_stats(net->stats, net->folded, n_subnets, net->T.row_len, (hipStream_t)hip_stream);
   if (e != hipSuccess) { delete net; return fail(SNA_E_HIP, "fold_stats: %s", hipGetErrorString(e)); }
   *out = net;
@@ -1328,6 +1373,39 @@ void sna_supernet_free(sna_supernet* net) {
 sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs,
                               const int32_t* req_cfg, int32_t n_requests, const void* inputs_dev,
                               float* logits_dev, void* hidden_dev, void* hip_stream) {
+  return forward_impl(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream, false);
+}
+
+sna_status sna_subnet_forward_static(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs,
+                                     const int32_t* req_cfg, int32_t n_requests, const void* inputs_dev,
+                                     float* logits_dev, void* hidden_dev, void* hip_stream) {
+  if (!net) return fail(SNA_E_NULL, "NULL argument");
+  if (net->tuning || net->calibrating || net->prof_on)
+    return fail(SNA_E_BATCH, "sna_subnet_forward_static: not while tuning, calibrating or profiling (those allocate)");
+  return forward_impl(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream, true);
+}
+
+int64_t sna_static_scratch_bytes(void) { return (int64_t)kStaticScratchBytes; }
+
+}  // extern "C"
+
+// RAII: point the handle's per-call scratch at another region for the duration of one call
+namespace {
+struct ScratchSwap {
+  sna_supernet* net;
+  char *arena, *partials;
+  size_t arena_bytes, partials_bytes;
+  ScratchSwap(sna_supernet* n, char* base, size_t total, size_t part) : net(n), arena(n->arena), partials(n->partials),
+      arena_bytes(n->arena_bytes), partials_bytes(n->partials_bytes) {
+    n->arena = base; n->arena_bytes = total - part; n->partials = base + (total - part); n->partials_bytes = part;
+  }
+  ~ScratchSwap() { net->arena = arena; net->partials = partials; net->arena_bytes = arena_bytes; net->partials_bytes = partials_bytes; }
+};
+}  // namespace
+
+static sna_status forward_impl(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_t n_cfgs, const int32_t* req_cfg,
+                               int32_t n_requests, const void* inputs_dev, float* logits_dev, void* hidden_dev,
+                               void* hip_stream, bool static_scratch) {
   if (!net || !cfgs || !req_cfg) return fail(SNA_E_NULL, "NULL argument");
   if (n_requests < 0 || n_requests > net->max_batch)
     return fail(SNA_E_BATCH, "n_requests %d outside [0, %d]", n_requests, net->max_batch);
@@ -1342,13 +1420,20 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   for (int r = 0; r < n_requests; ++r)
     if (req_cfg[r] < 0 || req_cfg[r] >= n_cfgs) return fail(SNA_E_BATCH, "req_cfg[%d]=%d outside [0, %d)", r, req_cfg[r], n_cfgs);
 
+  std::unique_ptr<ScratchSwap> swap;
+  if (static_scratch) {
+    char* base = static_scratch_base();
+    if (!base) return SNA_E_HIP;
+    swap.reset(new ScratchSwap(net, base, kStaticScratchBytes, kStaticPartialBytes));
+  }
   // The launch list depends on the routing, on the cfgs it names, on whether hidden states are
-  // wanted and on the tuning state; caller buffers only enter through patched pointer fields.
+  // wanted, on where the scratch lives and on the tuning state; caller buffers only enter through
+  // patched pointer fields.
   std::string key;
   const bool use_cache = net->plan_cache_on && !net->tuning && !net->calibrating;
   if (use_cache) {
     key.reserve((size_t)n_requests * 4 + 1024);
-    const int32_t head[3] = {n_requests, hidden_dev ? 1 : 0, net->split_mode};
+    const int32_t head[4] = {n_requests, hidden_dev ? 1 : 0, net->split_mode, static_scratch ? 1 : 0};
     key.append((const char*)head, sizeof(head));
     key.append((const char*)req_cfg, (size_t)n_requests * 4);
     std::vector<char> seen(n_cfgs, 0);
@@ -1405,7 +1490,13 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
     g.inbuf = cur; cur += align_up(in_b * g.n, 256);
     g.small = (float*)cur; cur += align_up(sm_b * g.n, 256);
   }
-  if ((size_t)(cur - net->arena) > net->arena_bytes) return fail(SNA_E_WORKSPACE, "arena overflow");
+  if ((size_t)(cur - net->arena) > net->arena_bytes) {
+    if (static_scratch)
+      return fail(SNA_E_WORKSPACE, "these %d requests need %zu bytes of activation scratch; the static scratch holds %zu "
+                  "(use sna_subnet_forward with a workspace, or a smaller batch)", n_requests, (size_t)(cur - net->arena),
+                  net->arena_bytes);
+    return fail(SNA_E_WORKSPACE, "arena overflow");
+  }
 
   if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3)
     f.pad_inputs(inputs_dev, req_off, a.family == SNA_FAMILY_RESNET && f.resnet_fused_stem());
@@ -1452,6 +1543,8 @@ sna_status sna_subnet_forward(sna_supernet* net, const sna_subnet_cfg* cfgs, int
   }
   return st;
 }
+
+extern "C" {
 
 sna_status sna_last_forward_info(const sna_supernet* net, int64_t* macs, int32_t* launches) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");

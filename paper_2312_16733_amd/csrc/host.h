@@ -81,7 +81,8 @@ struct sna_supernet {
   float* folded = nullptr;           // [n_subnets][2][row_len]
   char* arena = nullptr;
   size_t arena_bytes = 0;
-  char* partials = nullptr;          // kPartialBytes of fp32 K-chunk sums
+  char* partials = nullptr;          // fp32 K-chunk sums of split reductions (raw layer outputs while calibrating)
+  size_t partials_bytes = 0;
   int split_mode = 0;                // 0 auto, 1 never split a reduction over blocks, 2 always when chunked
   // tile variant measured best for a layer shape: (M, K_out, C_in, R*S, stride, parts) -> variant
   std::map<std::array<int, 6>, int> tuned;
