@@ -320,7 +320,8 @@ sna_status sna_profile_read(sna_supernet* net, double ms[SNA_N_KCLASS], int64_t 
                             double flops[SNA_N_KCLASS], double bytes[SNA_N_KCLASS]);
 const char* sna_profile_class_name(int32_t kclass);
 /* The launches recorded since the last sna_profile_read(), one text line each in
- * launch order: microseconds between the launch's two events, class name, then
+ * launch order: microseconds between the launch's two events, class name,
+ * "flops=" and "bytes=" (the launch's algorithmic work, active sizes only), then
  * for the grouped kernels the tile variant and every problem's active shape.
  * Syncs the events; does not clear them (sna_profile_read() does).  Writes at most
  * cap - 1 bytes plus a NUL into buf (host memory, may be NULL) and returns the

@@ -1213,6 +1213,7 @@ static sna_status execute_plan(sna_supernet* net, const Plan& plan, hipStream_t 
     if (e != hipSuccess) return fail(SNA_E_HIP, "launch failed: %s", hipGetErrorString(e));
     if (net->prof_on && a && b && hipEventRecord(b, stream) == hipSuccess) {
       ProfRec rec{op.kc, a, b, describe_op(op)};
+      rec.flops = op.flops; rec.bytes = op.bytes;
       if (op.type == PlanOp::IGEMM) { rec.igemm = true; rec.key = lead_key(op); rec.variant = op.variant; }
       net->prof_recs.push_back(std::move(rec));
       net->prof_flops[op.kc] += op.flops;
@@ -1731,13 +1732,13 @@ sna_status sna_profile_enable(sna_supernet* net, int32_t on) {
 int64_t sna_profile_read_launches(sna_supernet* net, char* buf, int64_t cap) {
   if (!net) { fail(SNA_E_NULL, "net is NULL"); return -1; }
   std::string out;
-  char t[96];
+  char t[160];
   for (const ProfRec& r : net->prof_recs) {
     hipError_t e = hipEventSynchronize(r.b);
     float ms = 0;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
     if (e != hipSuccess) { fail(SNA_E_HIP, "event: %s", hipGetErrorString(e)); return -1; }
-    snprintf(t, sizeof(t), "%.3f %s ", ms * 1e3, kClassNames[r.kc]);
+    snprintf(t, sizeof(t), "%.3f %s flops=%.0f bytes=%.0f ", ms * 1e3, kClassNames[r.kc], r.flops, r.bytes);
     out += t; out += r.what; out += '\n';
   }
   if (buf && cap > 0) {

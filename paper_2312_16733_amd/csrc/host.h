@@ -30,6 +30,7 @@ sna_status fail(sna_status st, const char* fmt, ...);
 
 struct ProfRec {
   int kc; hipEvent_t a, b; std::string what;
+  double flops = 0, bytes = 0;       // algorithmic work of the launch
   bool igemm = false;                // a matrix-kernel launch: `key` is the tuning key of its problem with the most work
   int variant = -1;                  // the tile variant that launch ran with
   std::array<int, 6> key{};

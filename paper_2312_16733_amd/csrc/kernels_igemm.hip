@@ -22,50 +22,11 @@
 // fp32 LDS tile so that residual loads and output stores are 16 bytes per lane.  Blocks are
 // renumbered so that consecutive tiles (which share activation rows) run on the same XCD.
 // A launch is grouped: each block finds its problem (one per subnet cfg) from its tile number.
-#include "common.h"
+#include "igemm_common.h"
 
-#include <type_traits>
+#include <atomic>
 
 namespace sna {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((address_space(3))) char lds_char;
-
-constexpr int BK = 64;             // reduction elements per LDS stage
-static_assert(BK == 64, "one LDS row holds one K step");
-constexpr int ROW_B = 128;         // bytes per LDS row (one K step of one tile row)
-
-// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
-// (vmcnt is split over bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at "no wait").
-constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
-
-template <int BM, int BN, int WARPS_M, int WARPS_N, int NS>
-struct IgemmCfg {
-  static constexpr int NWAVES = WARPS_M * WARPS_N, NTHREADS = 64 * NWAVES;
-  static constexpr int WTM = BM / WARPS_M, WTN = BN / WARPS_N;
-  static constexpr int TM = WTM / 32, TN = WTN / 32;
-  static constexpr int PASS_ROWS = NTHREADS / 8;                 // tile rows fetched per pass of the block
-  static constexpr int A_IT = (BM + PASS_ROWS - 1) / PASS_ROWS, B_IT = (BN + PASS_ROWS - 1) / PASS_ROWS;
-  static constexpr int STAGE_B = (BM + BN) * ROW_B;
-  static constexpr int EPI_STRIDE = WTN + 4;                     // floats per staged row
-  static constexpr int TILE_BYTES = NS * STAGE_B;
-  static constexpr int EPI_BYTES = NWAVES * 32 * EPI_STRIDE * 4;
-  static constexpr int SMEM = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
-};
-
-__device__ __forceinline__ unsigned long long low_bits(int n) { return n >= 64 ? ~0ull : (1ull << n) - 1ull; }   // n >= 0
-
-__device__ __forceinline__ u32x4 lds_read_b128(unsigned addr, int imm) {
-  u32x4 v;
-#if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm));
-#else
-  v = u32x4{addr, (unsigned)imm, 0u, 0u};      // host pass only parses this file
-#endif
-  return v;
-}
 
 // Waves per SIMD the register allocation must leave room for: tiles with short reductions are
 // launched with a small LDS request and then run that many blocks per CU.
@@ -935,13 +896,6 @@ static const Variant kVariants[] = {
     // 22..: one LDS stage, for short reductions: less LDS per block, more blocks per CU
     SNA_VARIANT(128, 128, 2, 2, 1), SNA_VARIANT(128, 64, 2, 2, 1), SNA_VARIANT(128, 96, 4, 1, 1), SNA_VARIANT(64, 128, 1, 4, 1),
     SNA_VARIANT(128, 32, 4, 1, 1), SNA_VARIANT(64, 64, 2, 2, 1),
-#ifdef SNA_EXTRA_VARIANTS
-    SNA_VARIANT(128, 64, 2, 2, 3), SNA_VARIANT(128, 64, 2, 2, 4), SNA_VARIANT(128, 128, 2, 2, 3), SNA_VARIANT(128, 96, 4, 1, 3),
-    SNA_WS_VARIANT(128, 128, 2, 2, 2), SNA_WS_VARIANT(128, 128, 2, 2, 4), SNA_WS_VARIANT(64, 128, 1, 4, 4),
-    SNA_WS_VARIANT(128, 64, 2, 2, 2), SNA_WS_VARIANT(64, 128, 1, 4, 2),
-    SNA_VARIANT(256, 128, 2, 2, 2), SNA_WS_VARIANT(256, 128, 2, 2, 3),
-    SNA_WS_VARIANT(128, 192, 2, 2, 2), SNA_WS_VARIANT(256, 128, 2, 2, 2), SNA_WS_VARIANT(256, 128, 4, 1, 3),
-#endif
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kLdsMax = 160 * 1024;
@@ -970,13 +924,13 @@ bool igemm_variant_ok(int variant, const ConvProblem& p) {
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s) {
   if (a.n == 0) return hipSuccess;
   if (variant < 0 || variant >= kNumVariants) return hipErrorInvalidValue;
-  static bool attr_done[kNumVariants][2] = {};
+  static std::atomic<bool> attr_done[kNumVariants][2];     // handles on several threads may get here together
   const Variant& v = kVariants[variant];
   void (*fn)(const ConvGroupArgs) = chunked ? v.fn_chunked : v.fn;
-  if (!attr_done[variant][chunked]) {
+  if (!attr_done[variant][chunked].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, v.slab ? kLdsMax : v.smem);
     if (e != hipSuccess) return e;
-    attr_done[variant][chunked] = true;
+    attr_done[variant][chunked].store(true, std::memory_order_release);
   }
   // a launch whose problems all have fewer K steps than the ring has stages only touches the
   // leading stages: asking for less LDS lets more blocks share a CU

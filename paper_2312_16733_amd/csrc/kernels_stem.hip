@@ -26,6 +26,8 @@
 // blocks per CU, so one block's MFMAs run under the other's epilogue and pool.
 #include "common.h"
 
+#include <atomic>
+
 namespace sna {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -288,11 +290,11 @@ hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s) {
   bool two = false;
   for (int i = 0; i < a.n; ++i) two = two || a.p[i].K > 32;
   void (*fn)(const StemPoolArgs) = two ? stem_pool_kernel<true> : stem_pool_kernel<false>;
-  static bool attr_done[2] = {false, false};
-  if (!attr_done[two]) {
+  static std::atomic<bool> attr_done[2];      // handles on several threads may get here together
+  if (!attr_done[two].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, stem::SMEM);
     if (e != hipSuccess) return e;
-    attr_done[two] = true;
+    attr_done[two].store(true, std::memory_order_release);
   }
   const int blocks = a.total_tiles < 512 ? a.total_tiles : 512;     // two persistent blocks per CU
   hipLaunchKernelGGL(fn, dim3(blocks), dim3(256), stem::SMEM, s, a);
