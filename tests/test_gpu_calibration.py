@@ -132,6 +132,61 @@ def test_calibration_mbv3_bf16(torch_mod):
     run_case(torch_mod, synth.MBV3Spec(), 16, (1, 15), 4, ("stem.sn", "first.sn1"), 1e-2, None, "bf16")
 
 
+# ------------------------------------------------------------------ fixed bars (they do not float with the oracle)
+def fixed_bar_case(torch, spec, n_cfg, cfg_ids, batch, stats_bar, logits_bar, mode, oracle_stats_max=None, oracle_logits_max=None):
+    """Calibration held to bars fixed in the test.  For bf16 the case is chosen shallow and the batch large, so
+    that storage rounding moves the oracle's own statistics and logits by well under the bars (asserted, so the
+    case cannot drift into the amplifying regime unnoticed); for fp32 the net is deep and the bar is the fp32 one."""
+    import oracle
+    import paper_2312_16733_amd as sna
+    W, S, C = setup(spec, n_cfg)
+    net = sna.Supernet(spec, W, S, n_cfg, batch)
+    try:
+        for ci in cfg_ids:
+            c = C[ci]
+            x = synth.make_inputs(spec, batch, c.in_h, c.in_w, 61 + ci)
+            want_stats, want_logits = oracle.calibrate(spec, W, S, c, x)
+            if mode == "bf16":
+                exact_stats, exact_logits = oracle.calibrate(spec, W, S, c, x, "f64")
+                own_s = max(table_errors(exact_stats, want_stats, S, c, untouched=False).values())
+                own_l = float(rel_err(want_logits, exact_logits).max())
+                assert own_s < oracle_stats_max and own_l < oracle_logits_max, ("case too ill-conditioned for a fixed bar", own_s, own_l)
+            net2 = sna.Supernet(spec, W, S, n_cfg, batch)        # every cfg calibrates on the seeded table
+            try:
+                got_logits = net2.calibrate(c, to_dev(torch, spec, x)).cpu().numpy()
+                torch.cuda.synchronize()
+                got_stats = net2.stats_table()
+            finally:
+                net2.close()
+            worst = table_errors(got_stats, want_stats, S, c)
+            es, el = max(worst.values()), float(rel_err(got_logits, want_logits).max())
+            say(spec.family, "fixed-bar calibration cfg", ci, "depth", list(c.depth), "batch", batch,
+                "stats err %.2e (bar %.0e), logits err %.2e (bar %.0e)" % (es, stats_bar, el, logits_bar))
+            assert es <= stats_bar, (max(worst, key=worst.get), es)
+            assert el <= logits_bar, el
+    finally:
+        net.close()
+
+
+def test_calibration_fixed_bar_bf16_shallow(torch_mod):
+    """bf16 families: two-stage SuperNets, batch 64: statistics of every layer within 1e-2, logits within the
+    2e-2 parity bar of the oracle's calibration."""
+    res = synth.ResNetSpec(n_classes=24, stem_ch=16, stage_ch=(32, 64), stage_stride=(1, 2), max_depth=(2, 2),
+                           depth_minus=(0, 1), res_choices=(32, 40))
+    fixed_bar_case(torch_mod, res, 4, (0, 3), 64, 1e-2, 2e-2, "bf16", 5e-3, 1.5e-2)
+    mb = synth.MBV3Spec(n_classes=24, stage_ch=(24, 40), stage_stride=(2, 2), stage_se=(False, True),
+                        stage_act=("relu", "hswish"), max_depth=(2, 2), depth_choices=(1, 2), res_choices=(32, 40),
+                        tail_ch=96, fc_ch=128)
+    fixed_bar_case(torch_mod, mb, 4, (0, 3), 64, 1e-2, 2e-2, "bf16", 5e-3, 1.5e-2)
+
+
+def test_calibration_fixed_bar_fp32_deep(torch_mod):
+    """fp32 family, 4 stages x 4 blocks (17 SubnetNorm layers in a row): the statistics kernels and the
+    normalise pass held to 1e-4 at depth, end to end."""
+    deep = synth.TinySpec(stage_ch=(32, 64, 96, 128), max_depth=(4, 4, 4, 4), depth_choices=(2, 3, 4), res_choices=(64,))
+    fixed_bar_case(torch_mod, deep, 6, (0, 3, 5), 8, 1e-4, 1e-4, "fp32")
+
+
 def test_calibration_rejects_what_it_cannot_do(torch_mod):
     import paper_2312_16733_amd as sna
     torch = torch_mod
