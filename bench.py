@@ -262,12 +262,13 @@ def main():
                 for i in range(3):
                     forward(ci, b)
                 torch.cuda.synchronize()
-                reps = 20
-                t1 = time.perf_counter()
-                for i in range(reps):
-                    forward(ci, b)
-                torch.cuda.synchronize()
-                d = (time.perf_counter() - t1) / reps
+                reps, d = 10, float("inf")
+                for group in range(3):           # the best of three groups: one stall on a shared box hits one group
+                    t1 = time.perf_counter()
+                    for i in range(reps):
+                        forward(ci, b)
+                    torch.cuda.synchronize()
+                    d = min(d, (time.perf_counter() - t1) / reps)
                 detail[f"b{b}_{tag}"] = {"images_per_s": b / d, "ms": d * 1e3,
                                          "gmacs_per_image": synth.subnet_macs(spec, C[ci]) / 1e9}
 
@@ -288,8 +289,11 @@ def main():
                 torch.cuda.synchronize()
                 return (time.perf_counter() - t1) / len(seq)
 
-            same = 0.5 * (timed([pair[0]] * reps) + timed([pair[1]] * reps))
-            alt = timed(list(pair) * (reps // 2))
+            def best(seq):
+                return min(timed(seq) for _ in range(3))
+
+            same = 0.5 * (best([pair[0]] * reps) + best([pair[1]] * reps))
+            alt = best(list(pair) * (reps // 2))
             act[f"b{b}"] = {"same_cfg_ms": same * 1e3, "alternating_ms": alt * 1e3,
                             "actuation_overhead_us": (alt - same) * 1e6, "cfgs": list(pair)}
         detail["actuation"] = act
@@ -303,11 +307,13 @@ def main():
             for i in range(3):
                 net.forward(cm, routem, xm, logits=logits)
             torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            for i in range(20):
-                net.forward(cm, routem, xm, logits=logits)
-            torch.cuda.synchronize()
-            d = (time.perf_counter() - t1) / 20
+            d = float("inf")
+            for group in range(3):
+                t1 = time.perf_counter()
+                for i in range(10):
+                    net.forward(cm, routem, xm, logits=logits)
+                torch.cuda.synchronize()
+                d = min(d, (time.perf_counter() - t1) / 10)
             detail["mixed64_zipf_res224"] = {"images_per_s": 64 / d, "ms": d * 1e3,
                                              "distinct_cfgs": int(len(set(routem.tolist()))),
                                              "launches": net.last_forward_info()[1]}

@@ -290,11 +290,16 @@ void sna_supernet_free(sna_supernet* net);
 /* How long reductions are laid out over blocks.  A conv / linear whose reduction is
  * longer than 1536 elements is summed in 2 or 4 chunks (a function of the layer's
  * active shape only), chunk sums added in order in fp32.  mode 0 (default): when a
- * layer has too few output tiles to fill the GPU, each chunk gets its own blocks
- * and a second kernel adds the chunk sums; otherwise one block walks all chunks.
- * mode 1: never spread chunks over blocks.  mode 2: always, when the layer is
- * chunked.  The logits have the same bits in all three modes; the knob exists
- * for timing and for checking that property.  Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
+ * layer has too few output tiles to fill the GPU (or a measured table entry says
+ * so), each chunk gets its own blocks, which leave fp32 chunk sums in the
+ * workspace; the block that arrives last at a tile adds them in chunk order and
+ * finishes the layer inside the same launch.  Otherwise one block walks all
+ * chunks.  mode 1: never spread chunks over blocks.  mode 2: always, when the
+ * layer is chunked.  mode 3: as 2, but the chunk sums are added by a separate
+ * reduction launch (the fall-back used when a launch has more tiles than the
+ * workspace has tile counters, 16384).  The logits have the same bits in all
+ * modes; the knob exists for timing and for checking that property.
+ * Errors: SNA_E_NULL, SNA_E_CFG_RANGE. */
 sna_status sna_set_k_split(sna_supernet* net, int32_t mode);
 
 /* Test / timing knob: force every conv / linear launch of the matrix kernel onto tile variant

@@ -61,6 +61,13 @@ struct ConvProblem {
   int parts, tiles_base;         // tiles = parts * tiles_base
   int kt_part, kt_chunk;
   unsigned long part_stride;     // bytes between the parts' fp32 outputs
+  // Reduction inside the matrix kernel (parts > 1, counters != nullptr): every block writes its raw fp32
+  // chunk sum to part_buf ([parts][M][K], part_stride bytes apart) and bumps its tile's counter; the block
+  // that arrives last adds the parts in chunk order and finishes the layer (scale, shift, res, act, y as
+  // for parts == 1), then puts the counter back to zero.  With counters == nullptr and parts > 1 the
+  // kernel writes the raw sums to y and splitk_reduce_kernel finishes the layer in a second launch.
+  float* part_buf;
+  int* counters;                 // [tiles_base] zero-initialised ints of this problem
 };
 
 struct ConvGroupArgs {
@@ -168,6 +175,9 @@ struct NormApplyArgs {
 
 // fp32 partial sums of split reductions: fixed region at the end of the workspace
 constexpr size_t kPartialBytes = (size_t)64 << 20;
+// tile counters of reductions that finish inside the matrix kernel: one per output tile of every such
+// problem in one launch
+constexpr size_t kTileCounters = 16384;
 
 // ---- launchers (defined in the .hip files) ---------------------------------------------------
 hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipStream_t s);

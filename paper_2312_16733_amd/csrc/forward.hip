@@ -166,6 +166,8 @@ struct Fwd {
     q.tiles_n = (q.K + bn - 1) / bn;
     q.tiles_base = ((q.M + bm - 1) / bm) * q.tiles_n;
     q.tiles = q.tiles_base * q.parts;
+    // reduction inside the matrix kernel: the chunk sums are kept tile by tile (bm x bn floats each)
+    if (q.counters) q.part_stride = (unsigned long)q.tiles_base * bm * bn * 4;
   }
 
   // Time every tile variant on this one problem (followed by its reduction launch when the
@@ -252,12 +254,16 @@ struct Fwd {
     }
     // Too few tiles for the chip: give every chunk its own blocks and sum them in a second launch
     // (a measured per-shape decision, where there is one, takes precedence).
-    const bool split_rule = net->split_mode == 2 || (net->split_mode == 0 && tiles_all < 256);
+    const bool split_rule = net->split_mode >= 2 || (net->split_mode == 0 && tiles_all < 256);
     std::vector<ConvProblem> reduce;
     char* part_cur = net->partials;
+    size_t counters_used = 0;
     for (size_t i = 0; i < n; ++i) {
       ConvProblem& q = ps[i];
-      const size_t part_bytes = align_up((size_t)chunks[i] * q.M * q.K * 4, 256);
+      // room for the chunk sums: row-major [chunks][M][K] for the separate reduction kernel; the matrix
+      // kernel's own reduction keeps them tile by tile, rows and columns padded to the tile (at most
+      // 128 x 192), so the larger of the two is reserved
+      const size_t part_bytes = align_up((size_t)chunks[i] * (q.M + 128) * (q.K + 192) * 4, 256);
       const bool can_split = chunks[i] > 1 && (size_t)(part_cur - net->partials) + part_bytes <= net->partials_bytes;
       ConvProblem r = q, qs = q;         // the reduction finishes the layer: keeps y, norm, residual, activation
       if (can_split) {
@@ -271,12 +277,27 @@ struct Fwd {
         qs.scale = nullptr; qs.shift = nullptr; qs.res = nullptr; qs.act = SNA_ACT_NONE;
       }
       bool split = can_split && split_rule;
+      // the reduction can finish inside the matrix launch when the layer's tile counters fit the table
+      // (mode 3 keeps the separate reduction kernel: a test knob for that path)
+      // (room is reserved for the smallest tile any variant has, 32 x 32; the slots are handed out below,
+      // once the tile variant is final)
+      const size_t counters_need = (size_t)((q.M + 31) / 32) * ((q.K + 31) / 32);
+      const bool fuse_reduce = can_split && net->split_mode != 3 && net->counters != nullptr &&
+                               (chunks[i] == 2 || chunks[i] == 4) && counters_used + counters_need <= kTileCounters;
+      if (fuse_reduce) {
+        qs = q;                                // the layer keeps y, norm, residual, activation
+        qs.parts = chunks[i];
+        qs.kt_part = q.kt_chunk;
+        qs.part_stride = r.part_stride;
+        qs.part_buf = (float*)part_cur;
+        qs.counters = net->counters + counters_used;
+      }
       if (can_split && net->split_mode == 0) {
         const auto key = tune_key(q, 0);
         if (net->tuning && !net->tuned_split.count(key)) {
           float t_one = 0.f, t_split = 0.f;
           net->tuned[tune_key(q, 1)] = measure_variants(q, true, nullptr, &t_one);
-          net->tuned[tune_key(q, chunks[i])] = measure_variants(qs, false, &r, &t_split);
+          net->tuned[tune_key(q, chunks[i])] = measure_variants(qs, false, fuse_reduce ? nullptr : &r, &t_split);
           net->tuned_split[key] = t_split < t_one ? 1 : 0;
         }
         auto it = net->tuned_split.find(key);
@@ -284,12 +305,14 @@ struct Fwd {
       }
       if (split) {
         q = qs;
-        reduce.push_back(r);
+        if (fuse_reduce) counters_used += counters_need;
+        else reduce.push_back(r);
         part_cur += part_bytes;
       }
       if (net->tuning && !net->tuned.count(tune_key(q, q.parts))) {
         float t = 0.f;
-        net->tuned[tune_key(q, q.parts)] = measure_variants(q, q.parts == 1 && chunks[i] > 1, split ? &r : nullptr, &t);
+        net->tuned[tune_key(q, q.parts)] = measure_variants(q, q.parts == 1 && chunks[i] > 1,
+                                                            (split && !fuse_reduce) ? &r : nullptr, &t);
       }
       auto it = net->tuned.find(tune_key(q, q.parts));
       if (it != net->tuned.end()) var[i] = it->second;
@@ -318,6 +341,19 @@ struct Fwd {
       }
     }
     if (err != hipSuccess) return;
+    {
+      size_t slot = 0;                       // counters of the reductions that finish inside the matrix launch
+      for (size_t i = 0; i < n; ++i)
+        if (ps[i].counters) {
+          ps[i].counters = net->counters + slot;
+          slot += (size_t)ps[i].tiles_base;
+          if ((size_t)ps[i].parts * ps[i].part_stride > align_up((size_t)ps[i].parts * (ps[i].M + 128) * (ps[i].K + 192) * 4, 256)) {
+            err = hipErrorInvalidValue;
+            return;
+          }
+        }
+      if (slot > kTileCounters) { err = hipErrorInvalidValue; return; }
+    }
     for (int chunked = 0; chunked < 2; ++chunked)
       for (int v = 0; v < igemm_num_variants(); ++v) {
         ConvGroupArgs a;
@@ -343,7 +379,7 @@ struct Fwd {
           flops += 2 * mac;
           // algorithmic bytes of the layer (the split path's partial sums are overhead, not counted)
           bytes += 2.0 * ((double)p.N * p.H * p.W * cc + (double)p.K * p.R * p.S * cc) +
-                   ((p.out_fp32 && p.parts == 1) ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K +
+                   ((p.out_fp32 && (p.parts == 1 || p.counters)) ? 4.0 : 2.0) * (double)p.M * p.K + 8.0 * p.K +
                    (p.res ? 2.0 * p.M * p.K : 0.0);
         }
         a.total_tiles = start;
@@ -1065,8 +1101,13 @@ sna_status Fwd::run_transformer(const void*, float* logits, void* hidden) {
   return SNA_OK;
 }
 
-static size_t folded_bytes(const ArchTables& T, int n_subnets) {
+// head of the workspace: the folded SubnetNorm tables, then the tile counters of reductions finished
+// inside the matrix kernel (zeroed at load; every launch leaves them at zero)
+static size_t folded_only_bytes(const ArchTables& T, int n_subnets) {
   return align_up((size_t)n_subnets * 2 * T.row_len * sizeof(float) + 256, 256);
+}
+static size_t folded_bytes(const ArchTables& T, int n_subnets) {
+  return folded_only_bytes(T, n_subnets) + align_up(kTileCounters * sizeof(int), 256);
 }
 static size_t per_request_arena(const ArchTables& T) {
   return (size_t)NBUF * align_up(T.per_image_elems * T.esz, 256) + align_up(T.in_elems_max * T.esz, 256) +
@@ -1354,6 +1395,11 @@ sna_status sna_supernet_load(const sna_arch_desc* arch, const void* weights_dev,
   net->arena_bytes = workspace_bytes - folded_bytes(net->T, n_subnets) - kPartialBytes;
   net->partials = net->arena + net->arena_bytes / 256 * 256;
   net->partials_bytes = kPartialBytes;
+  net->counters = (int*)(net->workspace + folded_only_bytes(net->T, n_subnets));
+  if (hipMemsetAsync(net->counters, 0, kTileCounters * sizeof(int), (hipStream_t)hip_stream) != hipSuccess) {
+    delete net;
+    return fail(SNA_E_HIP, "clearing the tile counters failed");
+  }
   net->n_subnets = n_subnets;
   net->max_batch = max_batch;
   // resolve this device's static scratch now, outside any stream capture a later forward may run under
@@ -1717,7 +1763,7 @@ sna_status sna_set_tile_variant(sna_supernet* net, int32_t variant) {
 
 sna_status sna_set_k_split(sna_supernet* net, int32_t mode) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
-  if (mode < 0 || mode > 2) return fail(SNA_E_CFG_RANGE, "k split mode %d", mode);
+  if (mode < 0 || mode > 3) return fail(SNA_E_CFG_RANGE, "k split mode %d", mode);
   net->split_mode = mode;
   net->plans.clear();
   return SNA_OK;

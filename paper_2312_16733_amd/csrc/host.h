@@ -84,6 +84,7 @@ struct sna_supernet {
   size_t arena_bytes = 0;
   char* partials = nullptr;          // fp32 K-chunk sums of split reductions (raw layer outputs while calibrating)
   size_t partials_bytes = 0;
+  int* counters = nullptr;           // kTileCounters ints, all zero between launches (in-kernel split reductions)
   int split_mode = 0;                // 0 auto, 1 never split a reduction over blocks, 2 always when chunked
   // tile variant measured best for a layer shape: (M, K_out, C_in, R*S, stride, parts) -> variant
   std::map<std::array<int, 6>, int> tuned;

@@ -34,6 +34,115 @@ constexpr int igemm_min_waves(int bm, int bn) {
   return bm * bn > 128 * 128 ? 2 : (bm * bn >= 128 * 128 ? 3 : (bm * bn >= 128 * 96 ? 4 : 5));
 }
 
+// Accesses that are coherent across the chip without cache-wide flushes: relaxed atomics at agent
+// scope.  Such a store is written through to memory and such a load is not served from the CU's own
+// cache.  The chunk sums that blocks on different XCDs hand to each other go through these; fences
+// instead would write back and invalidate the whole L2 of an XCD under the feet of its other blocks
+// (measured: forwards at batch 16 lost 15-25 %).  8 bytes per access is the widest atomic there is.
+__device__ __forceinline__ void store_f8_agent(float* ptr, const float* v) {      // 8 floats, 32-byte aligned
+  unsigned long long* q = (unsigned long long*)ptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const unsigned long long w = (unsigned long long)__float_as_uint(v[2 * i]) |
+                                 ((unsigned long long)__float_as_uint(v[2 * i + 1]) << 32);
+    __hip_atomic_store(q + i, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ __forceinline__ void load_f8_agent(const float* ptr, float4& lo, float4& hi) {
+  const unsigned long long* q = (const unsigned long long*)ptr;
+  unsigned long long w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = __hip_atomic_load(q + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  lo = make_float4(__uint_as_float((unsigned)w[0]), __uint_as_float((unsigned)(w[0] >> 32)),
+                   __uint_as_float((unsigned)w[1]), __uint_as_float((unsigned)(w[1] >> 32)));
+  hi = make_float4(__uint_as_float((unsigned)w[2]), __uint_as_float((unsigned)(w[2] >> 32)),
+                   __uint_as_float((unsigned)w[3]), __uint_as_float((unsigned)(w[3] >> 32)));
+}
+
+// Sum of the fp32 chunk sums of output row m, channels k .. k+7, in chunk order, then SubnetNorm scale /
+// shift, residual and activation exactly as the fused epilogue does: the same bits as one block walking
+// all chunks.  `src` points at part 0's row-major [M][K] sums.  Used by the reduction kernel and by the
+// matrix kernel's own last-arriving block.
+// AGENT: `src0` already points at this octet inside part 0 (the matrix kernel's tile-major layout).
+template <bool AGENT>
+__device__ __forceinline__ void reduce_octet(const ConvProblem& p, const float* src0, int m, int k) {
+  // all loads first (at most 4 chunks), then the sums in chunk order
+  const float* src = AGENT ? src0 : src0 + (long)m * p.K + k;
+  float4 pa[4], pb[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (c < p.parts) {
+      const float* sp = (const float*)((const char*)src + (size_t)c * p.part_stride);
+      if (AGENT) {
+        load_f8_agent(sp, pa[c], pb[c]);      // written by other blocks of this launch
+      } else {
+        pa[c] = *(const float4*)sp;
+        pb[c] = *(const float4*)(sp + 4);
+      }
+    }
+  }
+  float4 sc0 = make_float4(1.f, 1.f, 1.f, 1.f), sc1 = sc0, sh0 = make_float4(0.f, 0.f, 0.f, 0.f), sh1 = sh0;
+  // the per-channel vectors are only guaranteed 4-byte alignment
+  auto load8 = [&](const float* v, float4& lo, float4& hi) {
+    if (((size_t)v & 15) == 0) {
+      lo = *(const float4*)(v + k);
+      hi = *(const float4*)(v + k + 4);
+    } else {
+      lo = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+      hi = make_float4(v[k + 4], v[k + 5], v[k + 6], v[k + 7]);
+    }
+  };
+  if (p.scale) load8(p.scale, sc0, sc1);
+  if (p.shift) load8(p.shift, sh0, sh1);
+  uint4 r4 = make_uint4(0, 0, 0, 0);
+  if (p.res) r4 = *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k);
+  float val[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (c < p.parts) {
+      val[0] = val[0] + pa[c].x; val[1] = val[1] + pa[c].y; val[2] = val[2] + pa[c].z; val[3] = val[3] + pa[c].w;
+      val[4] = val[4] + pb[c].x; val[5] = val[5] + pb[c].y; val[6] = val[6] + pb[c].z; val[7] = val[7] + pb[c].w;
+    }
+  }
+  const float scv[8] = {sc0.x, sc0.y, sc0.z, sc0.w, sc1.x, sc1.y, sc1.z, sc1.w};
+  const float shv[8] = {sh0.x, sh0.y, sh0.z, sh0.w, sh1.x, sh1.y, sh1.z, sh1.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = fmaf(val[e], scv[e], shv[e]);
+  float rv[8];
+  if (p.res) {
+    const unsigned ru[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      rv[2 * e] = __uint_as_float(ru[e] << 16);
+      rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
+    }
+    if (!p.res_after_act) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[e] += rv[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], p.act);
+  if (p.res && p.res_after_act) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) val[e] += rv[e];
+  }
+  if (p.out_fp32) {
+    float* yo = (float*)p.y + (long)m * p.y_stride + k;
+    *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
+    *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+  } else {
+    uint4 o;
+    o.x = pack_bf16x2(val[0], val[1]);
+    o.y = pack_bf16x2(val[2], val[3]);
+    o.z = pack_bf16x2(val[4], val[5]);
+    o.w = pack_bf16x2(val[6], val[7]);
+    *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
+  }
+}
+
 // WS (wave-specialised): the block has twice the waves; the second half only fetches (address
 // arithmetic, global->LDS loads, the wait for them), the first half only computes, and the two
 // meet at the one barrier per K step.  A fetching wave stalled on the texture path no longer
@@ -251,12 +360,15 @@ void igemm_kernel(const ConvGroupArgs args) {
   // SubnetNorm scale / shift of this lane's output columns, requested behind the first stages' loads so
   // that they arrive under the main loop
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  // reduction finished inside this launch: the blocks store bare chunk sums, the last one to arrive at a
+  // tile applies scale / shift / residual / activation after adding them up
+  const bool in_kernel_reduce = p.parts > 1 && p.counters != nullptr;
   float sc[TN], sh[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int k = n0 + wn * WTN + j * 32 + col_l;
-    sc[j] = (do_math && p.scale && k < p.K) ? p.scale[k] : 1.f;
-    sh[j] = (do_math && p.shift && k < p.K) ? p.shift[k] : 0.f;
+    sc[j] = (do_math && !in_kernel_reduce && p.scale && k < p.K) ? p.scale[k] : 1.f;
+    sh[j] = (do_math && !in_kernel_reduce && p.shift && k < p.K) ? p.shift[k] : 0.f;
   }
 
   // CHUNKED: the reduction is summed in chunks of p.kt_chunk steps, each accumulated from zero and
@@ -386,9 +498,17 @@ void igemm_kernel(const ConvGroupArgs args) {
         }
         if (m < p.M && k < p.K) {
           if (F32) {
-            float* yo = (float*)((char*)p.y + (size_t)part * p.part_stride) + (long)m * p.y_stride + k;
-            *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
-            *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+            if (in_kernel_reduce) {
+              // tile-major: every tile's sums fill whole cache lines of their own, so that no block ever
+              // pulls a line into its L2 that another tile's blocks have yet to write
+              float* yo = (float*)((char*)p.part_buf + (size_t)part * p.part_stride) + (size_t)local * (BM * BN) +
+                          (m - m0) * BN + (k - n0);
+              store_f8_agent(yo, val);
+            } else {
+              float* yo = (float*)((char*)p.y + (size_t)part * p.part_stride) + (long)m * p.y_stride + k;
+              *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
+              *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
+            }
           } else {
             uint4 o;
             o.x = pack_bf16x2(val[0], val[1]);
@@ -407,7 +527,32 @@ void igemm_kernel(const ConvGroupArgs args) {
   typedef integral_constant<bool, false> no_t;
 #define SNA_EPI(A, R) epilogue(integral_constant<int, A>{}, integral_constant<int, R>{}, no_t{})
   const int res_mode = p.res ? (p.res_after_act ? 2 : 1) : 0;
-  if (p.out_fp32) {                                            // logits: no activation, no residual
+  if (in_kernel_reduce) {
+    epilogue(integral_constant<int, SNA_ACT_NONE>{}, integral_constant<int, 0>{}, yes_t{});      // bare chunk sums to part_buf
+    // Count arrivals at this tile.  The chunk sums went out as write-through agent-scope stores; once
+    // every thread's stores have completed, the block's one atomic publishes them.  The block that sees
+    // parts - 1 earlier arrivals is the last and owns the tile from here on (nobody waits for anybody).
+    // It puts the counter back to zero for the next launch that uses it.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    int* const flag = (int*)smem;               // the ring is dead by now
+    if (threadIdx.x == 0) {
+      int* const cnt = p.counters + local;
+      const int seen = atomicAdd(cnt, 1);
+      const int last = seen == p.parts - 1;
+      if (last) atomicExch(cnt, 0);
+      *flag = last;
+    }
+    __syncthreads();
+    if (*flag == 0) return;
+    constexpr int OCT_T = BN / 8;
+    const int nthr = 64 * NW;                   // fetching waves of a wave-specialised block have left
+    for (int id = threadIdx.x; id < BM * OCT_T; id += nthr) {
+      const int row = id / OCT_T, oct = id - row * OCT_T;
+      const int m = m0 + row, k = n0 + oct * 8;
+      if (m < p.M && k < p.K) reduce_octet<true>(p, p.part_buf + (size_t)local * (BM * BN) + row * BN + oct * 8, m, k);
+    }
+  } else if (p.out_fp32) {                                     // logits: no activation, no residual
     if (p.act == SNA_ACT_NONE && res_mode == 0) epilogue(integral_constant<int, SNA_ACT_NONE>{}, integral_constant<int, 0>{}, yes_t{});
   } else if (p.act == SNA_ACT_RELU) {
     if (res_mode == 0) SNA_EPI(SNA_ACT_RELU, 0); else if (res_mode == 1) SNA_EPI(SNA_ACT_RELU, 1); else SNA_EPI(SNA_ACT_RELU, 2);
@@ -789,77 +934,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvGroupArgs 
   if (idx >= (long)p.M * k8n) return;
   const int m = (int)(idx / k8n);
   const int k = (int)(idx - (long)m * k8n) * 8;
-  // all loads first (at most 4 chunks), then the sums in chunk order
-  const float* src = (const float*)p.x + (long)m * p.K + k;
-  float4 pa[4], pb[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (c < p.parts) {
-      const float* sp = (const float*)((const char*)src + (size_t)c * p.part_stride);
-      pa[c] = *(const float4*)sp;
-      pb[c] = *(const float4*)(sp + 4);
-    }
-  }
-  float4 sc0 = make_float4(1.f, 1.f, 1.f, 1.f), sc1 = sc0, sh0 = make_float4(0.f, 0.f, 0.f, 0.f), sh1 = sh0;
-  // the per-channel vectors are only guaranteed 4-byte alignment
-  auto load8 = [&](const float* v, float4& lo, float4& hi) {
-    if (((size_t)v & 15) == 0) {
-      lo = *(const float4*)(v + k);
-      hi = *(const float4*)(v + k + 4);
-    } else {
-      lo = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
-      hi = make_float4(v[k + 4], v[k + 5], v[k + 6], v[k + 7]);
-    }
-  };
-  if (p.scale) load8(p.scale, sc0, sc1);
-  if (p.shift) load8(p.shift, sh0, sh1);
-  uint4 r4 = make_uint4(0, 0, 0, 0);
-  if (p.res) r4 = *(const uint4*)((const bf16_t*)p.res + (long)m * p.res_stride + k);
-  float val[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) val[e] = 0.f;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (c < p.parts) {
-      val[0] = val[0] + pa[c].x; val[1] = val[1] + pa[c].y; val[2] = val[2] + pa[c].z; val[3] = val[3] + pa[c].w;
-      val[4] = val[4] + pb[c].x; val[5] = val[5] + pb[c].y; val[6] = val[6] + pb[c].z; val[7] = val[7] + pb[c].w;
-    }
-  }
-  const float scv[8] = {sc0.x, sc0.y, sc0.z, sc0.w, sc1.x, sc1.y, sc1.z, sc1.w};
-  const float shv[8] = {sh0.x, sh0.y, sh0.z, sh0.w, sh1.x, sh1.y, sh1.z, sh1.w};
-#pragma unroll
-  for (int e = 0; e < 8; ++e) val[e] = fmaf(val[e], scv[e], shv[e]);
-  float rv[8];
-  if (p.res) {
-    const unsigned ru[4] = {r4.x, r4.y, r4.z, r4.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      rv[2 * e] = __uint_as_float(ru[e] << 16);
-      rv[2 * e + 1] = __uint_as_float(ru[e] & 0xffff0000u);
-    }
-    if (!p.res_after_act) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) val[e] += rv[e];
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) val[e] = apply_act(val[e], p.act);
-  if (p.res && p.res_after_act) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) val[e] += rv[e];
-  }
-  if (p.out_fp32) {
-    float* yo = (float*)p.y + (long)m * p.y_stride + k;
-    *(float4*)yo = make_float4(val[0], val[1], val[2], val[3]);
-    *(float4*)(yo + 4) = make_float4(val[4], val[5], val[6], val[7]);
-  } else {
-    uint4 o;
-    o.x = pack_bf16x2(val[0], val[1]);
-    o.y = pack_bf16x2(val[2], val[3]);
-    o.z = pack_bf16x2(val[4], val[5]);
-    o.w = pack_bf16x2(val[6], val[7]);
-    *(uint4*)((bf16_t*)p.y + (long)m * p.y_stride + k) = o;
-  }
+  reduce_octet<false>(p, (const float*)p.x, m, k);
 }
 
 hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s) {
