@@ -67,19 +67,30 @@ def measure(net, cfgs_c, route, x, logits, reps):
 
 
 def report(rows, title, fh):
+    """One line per distinct launch (class + shapes), in order of first appearance, with how often the
+    forward issues it and its mean time; totals over all launches below."""
     fh.write(f"## {title}\n")
-    fh.write(f"{'us':>8} {'class':<18} {'GFLOP':>8} {'MB':>8} {'AI':>6} {'bound':<5} {'achieved':>12} {'frac':>6}  launch\n")
-    tot_us = tot_f = tot_b = 0.0
-    ideal_us = 0.0
+    fh.write(f"{'n':>3} {'us':>7} {'class':<18} {'GFLOP':>8} {'MB':>8} {'AI':>5} {'bound':<5} {'achieved':>13} {'frac':>6}  launch\n")
+    tot_us = tot_f = tot_b = ideal_us = 0.0
+    merged, order = {}, []
     for us, cls, flops, nbytes, what in rows:
-        bound, ach, frac = grade(flops, nbytes, us)
-        unit = "TFLOP/s" if bound == "mfma" else "GB/s"
-        ai = flops / nbytes if nbytes else 0.0
-        fh.write(f"{us:8.2f} {cls:<18} {flops / 1e9:8.3f} {nbytes / 1e6:8.3f} {ai:6.0f} {bound:<5} {ach:8.1f} {unit:<7} {frac:6.3f}  {what}\n")
+        what = what.replace("chunked=0 ", "").replace(" parts=1", "")
+        key = (cls, flops, nbytes, what)
+        if key not in merged:
+            merged[key] = []
+            order.append(key)
+        merged[key].append(us)
         tot_us += us
         tot_f += flops
         tot_b += nbytes
         ideal_us += max(flops / (PEAK_TFLOPS * 1e12), nbytes / (PEAK_GBS * 1e9)) * 1e6
+    for key in order:
+        cls, flops, nbytes, what = key
+        us = float(np.mean(merged[key]))
+        bound, ach, frac = grade(flops, nbytes, us)
+        unit = "TFLOP/s" if bound == "mfma" else "GB/s"
+        ai = flops / nbytes if nbytes else 0.0
+        fh.write(f"{len(merged[key]):3d} {us:7.2f} {cls:<18} {flops / 1e9:8.3f} {nbytes / 1e6:8.3f} {ai:5.0f} {bound:<5} {ach:7.1f} {unit:<7} {frac:6.3f}  {what}\n")
     fh.write(f"total: {len(rows)} launches, {tot_us:.1f} us, {tot_f / 1e9:.2f} GFLOP ({tot_f / tot_us / 1e6:.0f} TFLOP/s), "
              f"{tot_b / 1e6:.1f} MB ({tot_b / tot_us / 1e3:.0f} GB/s); sum of per-launch roofline times {ideal_us:.1f} us "
              f"= {ideal_us / tot_us:.3f} of the measured time\n\n")
