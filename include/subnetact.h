@@ -275,9 +275,11 @@ sna_status sna_subnet_calibrate(sna_supernet* net, const sna_subnet_cfg* cfg,
 /* Number of layer shapes with a measured tile variant on this handle. */
 int32_t sna_tuned_count(const sna_supernet* net);
 
-/* The measured choices as text, one per line ("v M K C RS stride parts variant" for a tile
- * variant, "s M K C RS stride 0 flag" for the K-split decision), so that a deployment can ship
- * them instead of measuring at every start.  Export writes at most `cap` bytes (host memory,
+/* The measured choices as text, one per line ("v M K C RS stride parts twins variant" for a tile
+ * variant, "s M K C RS stride 0 twins flag" for the K-split decision; twins = problems of this
+ * shape that share the launch, e.g. 3 for a layer's Q, K and V projections; a line without the
+ * twins field is read as twins = 1), so that a deployment can ship them instead of measuring at
+ * every start.  Export writes at most `cap` bytes (host memory,
  * NUL-terminated when it fits) and returns the size needed, excluding the NUL.  Import adds
  * the lines of `text` (host memory, `len` bytes) to the handle's tables, replacing entries for
  * the same shape; lines it cannot parse or that name an unknown variant give SNA_E_CFG_RANGE and

@@ -174,7 +174,7 @@ struct Fwd {
   // reduction is split over blocks) and return the fastest; *best_ms gets its time per run.
   // Runs the problem for real (outputs are rewritten with the same values each time) and
   // synchronises on the stream.
-  int measure_variants(const ConvProblem& q, bool chunked, const ConvProblem* reduce, float* best_ms) {
+  int measure_variants(const ConvProblem& q, bool chunked, const ConvProblem* reduce, float* best_ms, int copies = 1) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { err = hipErrorUnknown; return 0; }
     ConvGroupArgs ra;
@@ -190,11 +190,14 @@ struct Fwd {
     for (int v = 0; v < igemm_num_variants() && err == hipSuccess; ++v) {
       if (!igemm_variant_ok(v, q)) continue;
       ConvGroupArgs a;
-      a.n = 1;
-      a.p[0] = q;
-      place(a.p[0], v);
-      a.p[0].tile_start = 0;
-      a.total_tiles = a.p[0].tiles;
+      a.n = copies < 1 ? 1 : (copies > SNA_MAX_GROUPS ? SNA_MAX_GROUPS : copies);   // twins: the launch carries that many tiles
+      a.total_tiles = 0;
+      for (int c = 0; c < a.n; ++c) {
+        a.p[c] = q;
+        place(a.p[c], v);
+        a.p[c].tile_start = a.total_tiles;
+        a.total_tiles += a.p[c].tiles;
+      }
       auto once = [&] {
         err = launch_igemm(a, v, chunked, stream);
         if (err == hipSuccess && reduce) err = launch_splitk_reduce(ra, stream);
@@ -219,8 +222,10 @@ struct Fwd {
     return best < 0 ? 0 : best;
   }
 
-  static std::array<int, 6> tune_key(const ConvProblem& q, int parts) {
-    return {q.M, q.K, q.C, q.R * q.S, q.stride, parts};
+  // `twins`: how many problems of this very shape share the launch (the Q, K and V projections of a layer):
+  // a launch with three times the tiles wants another tile than the same shape launched alone
+  static TuneKey tune_key(const ConvProblem& q, int parts, int twins) {
+    return {q.M, q.K, q.C, q.R * q.S, q.stride, parts, twins};
   }
 
   // K chunking, a function of the reduction length only: the same layer of the same subnet is
@@ -233,7 +238,23 @@ struct Fwd {
   void run_igemm(std::vector<ConvProblem>& ps, bool unify = false) {
     if (ps.empty()) return;
     const size_t n = ps.size();
-    std::vector<int> var(n), chunks(n);
+    std::vector<int> var(n), chunks(n), twins(n, 1);
+    for (size_t i = 0; i < n; ++i) {
+      int t = 0;
+      for (size_t j = 0; j < n; ++j)
+        t += ps[j].M == ps[i].M && ps[j].K == ps[i].K && ps[j].C == ps[i].C && ps[j].R == ps[i].R && ps[j].S == ps[i].S &&
+             ps[j].stride == ps[i].stride;
+      twins[i] = t;
+    }
+    // the table's entry for this shape with as many twins, else with the nearest smaller count (a mixed batch can
+    // bring more same-shaped problems together than any single-subnet call that was measured)
+    auto find_tuned = [&](const ConvProblem& q, int parts, int tw) {
+      for (; tw >= 1; --tw) {
+        auto it = net->tuned.find(tune_key(q, parts, tw));
+        if (it != net->tuned.end()) return it;
+      }
+      return net->tuned.end();
+    };
     long tiles_all = 0;
     for (size_t i = 0; i < n; ++i) {
       ConvProblem& q = ps[i];
@@ -244,7 +265,7 @@ struct Fwd {
       }
       q.parts = 1;
       q.kt_part = 1 << 30;
-      auto it = net->tuned.find(tune_key(q, 1));
+      auto it = find_tuned(q, 1, twins[i]);
       var[i] = it != net->tuned.end() ? it->second : pick_variant(q.M, q.K, q.C * q.R * q.S);
       place(q, var[i]);
       tiles_all += q.tiles_base;
@@ -293,14 +314,16 @@ struct Fwd {
         qs.counters = net->counters + counters_used;
       }
       if (can_split && net->split_mode == 0) {
-        const auto key = tune_key(q, 0);
+        const auto key = tune_key(q, 0, twins[i]);
         if (net->tuning && !net->tuned_split.count(key)) {
+          // (a split layer is timed alone: copies of it would share its tile counters)
           float t_one = 0.f, t_split = 0.f;
-          net->tuned[tune_key(q, 1)] = measure_variants(q, true, nullptr, &t_one);
-          net->tuned[tune_key(q, chunks[i])] = measure_variants(qs, false, fuse_reduce ? nullptr : &r, &t_split);
+          net->tuned[tune_key(q, 1, twins[i])] = measure_variants(q, true, nullptr, &t_one);
+          net->tuned[tune_key(q, chunks[i], twins[i])] = measure_variants(qs, false, fuse_reduce ? nullptr : &r, &t_split);
           net->tuned_split[key] = t_split < t_one ? 1 : 0;
         }
-        auto it = net->tuned_split.find(key);
+        auto it = net->tuned_split.end();
+        for (int tw = twins[i]; tw >= 1 && it == net->tuned_split.end(); --tw) it = net->tuned_split.find(tune_key(q, 0, tw));
         if (it != net->tuned_split.end()) split = it->second != 0;
       }
       if (split) {
@@ -309,12 +332,13 @@ struct Fwd {
         else reduce.push_back(r);
         part_cur += part_bytes;
       }
-      if (net->tuning && !net->tuned.count(tune_key(q, q.parts))) {
+      if (net->tuning && !net->tuned.count(tune_key(q, q.parts, twins[i]))) {
         float t = 0.f;
-        net->tuned[tune_key(q, q.parts)] = measure_variants(q, q.parts == 1 && chunks[i] > 1,
-                                                            (split && !fuse_reduce) ? &r : nullptr, &t);
+        net->tuned[tune_key(q, q.parts, twins[i])] = measure_variants(q, q.parts == 1 && chunks[i] > 1,
+                                                                      (split && !fuse_reduce) ? &r : nullptr, &t,
+                                                                      q.parts == 1 ? twins[i] : 1);
       }
-      auto it = net->tuned.find(tune_key(q, q.parts));
+      auto it = find_tuned(q, q.parts, twins[i]);
       if (it != net->tuned.end()) var[i] = it->second;
       if (net->forced_variant >= 0 && igemm_variant_ok(net->forced_variant, q)) var[i] = net->forced_variant;
       if (!igemm_variant_ok(var[i], q)) var[i] = pick_variant(q.M, q.K, q.C * q.R * q.S);
@@ -1190,9 +1214,9 @@ static void visit_io_pointers(const PlanOp& op, F&& f) {
 }
 
 // Run a launch list on the stream, with the per-launch event brackets when timing is enabled.
-// Tuning key (M, K_out, C_in, taps, stride, parts) of the problem with the most work in a matrix-kernel
+// Tuning key (M, K_out, C_in, taps, stride, parts, same-shaped problems in the launch) of the problem with the most work in a matrix-kernel
 // launch: the one whose tile variant the whole launch uses.
-static std::array<int, 6> lead_key(const PlanOp& op) {
+static TuneKey lead_key(const PlanOp& op) {
   const ConvGroupArgs& a = *(const ConvGroupArgs*)op.args.data();
   int lead = 0;
   double lead_work = -1;
@@ -1202,7 +1226,12 @@ static std::array<int, 6> lead_key(const PlanOp& op) {
     if (work > lead_work) { lead_work = work; lead = i; }
   }
   const ConvProblem& q = a.p[lead];
-  return {q.M, q.K, q.C, q.R * q.S, q.stride, q.parts};
+  int twins = 0;
+  for (int i = 0; i < a.n; ++i) {
+    const ConvProblem& o = a.p[i];
+    twins += o.M == q.M && o.K == q.K && o.C == q.C && o.R == q.R && o.S == q.S && o.stride == q.stride;
+  }
+  return {q.M, q.K, q.C, q.R * q.S, q.stride, q.parts, twins};
 }
 
 // One line of text for a launch: what the per-launch profile lists beside its time.
@@ -1609,7 +1638,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
                            int32_t n_requests, const void* inputs_dev, float* logits_dev, void* hidden_dev,
                            void* hip_stream) {
   if (!net) return fail(SNA_E_NULL, "net is NULL");
-  std::set<std::array<int, 6>> known;
+  std::set<TuneKey> known;
   for (const auto& kv : net->tuned) known.insert(kv.first);
   // Step 1: every new layer shape alone, launched back to back with each variant (also decides
   // whether a chunked reduction is split over blocks).
@@ -1631,7 +1660,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
   net->plan_cache_on = false;
   net->prof_on = true;
   const int nv = igemm_num_variants(), rounds = 7;
-  std::map<std::array<int, 6>, std::vector<std::vector<double>>> samples;   // key -> [variant][round]
+  std::map<TuneKey, std::vector<std::vector<double>>> samples;   // key -> [variant][round]
   for (int round = 0; round <= rounds && st == SNA_OK; ++round)             // round 0 warms up, not recorded
     for (int v = 0; v < nv && st == SNA_OK; ++v) {
       net->forced_variant = v;
@@ -1639,7 +1668,7 @@ sna_status sna_subnet_tune(sna_supernet* net, const sna_subnet_cfg* cfgs, int32_
       net->ev_used = 0;
       st = sna_subnet_forward(net, cfgs, n_cfgs, req_cfg, n_requests, inputs_dev, logits_dev, hidden_dev, hip_stream);
       if (st != SNA_OK) break;
-      std::map<std::array<int, 6>, double> sum;
+      std::map<TuneKey, double> sum;
       for (const ProfRec& r : net->prof_recs) {
         if (!r.igemm || r.variant != v) continue;       // a variant that cannot run this shape was not applied
         float ms = 0;
@@ -1708,13 +1737,13 @@ int64_t sna_tuning_export(const sna_supernet* net, char* buf, int64_t cap) {
   std::string out;
   char line[128];
   for (const auto& kv : net->tuned) {
-    snprintf(line, sizeof(line), "v %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
-             kv.first[4], kv.first[5], kv.second);
+    snprintf(line, sizeof(line), "v %d %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
+             kv.first[4], kv.first[5], kv.first[6], kv.second);
     out += line;
   }
   for (const auto& kv : net->tuned_split) {
-    snprintf(line, sizeof(line), "s %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
-             kv.first[4], kv.first[5], kv.second);
+    snprintf(line, sizeof(line), "s %d %d %d %d %d %d %d %d\n", kv.first[0], kv.first[1], kv.first[2], kv.first[3],
+             kv.first[4], kv.first[5], kv.first[6], kv.second);
     out += line;
   }
   if (buf && cap > 0) {
@@ -1727,7 +1756,7 @@ int64_t sna_tuning_export(const sna_supernet* net, char* buf, int64_t cap) {
 
 sna_status sna_tuning_import(sna_supernet* net, const char* text, int64_t len) {
   if (!net || !text) return fail(SNA_E_NULL, "NULL argument");
-  std::map<std::array<int, 6>, int> tv, ts;
+  std::map<TuneKey, int> tv, ts;
   const std::string all(text, (size_t)(len < 0 ? 0 : len));
   size_t pos = 0;
   while (pos < all.size()) {
@@ -1736,11 +1765,14 @@ sna_status sna_tuning_import(sna_supernet* net, const char* text, int64_t len) {
     const std::string ln = all.substr(pos, end - pos);
     pos = end + 1;
     if (ln.empty() || ln[0] == '#') continue;
-    char kind = 0;
-    int k[6], val = 0;
-    if (sscanf(ln.c_str(), "%c %d %d %d %d %d %d %d", &kind, &k[0], &k[1], &k[2], &k[3], &k[4], &k[5], &val) != 8)
-      return fail(SNA_E_CFG_RANGE, "tuning line not understood: %s", ln.c_str());
-    const std::array<int, 6> key = {k[0], k[1], k[2], k[3], k[4], k[5]};
+    char kind = 0, extra = 0;
+    int k[7], val = 0;
+    // key of seven numbers and the choice; a line with six (written before the twin count existed) means one twin
+    const int got = sscanf(ln.c_str(), "%c %d %d %d %d %d %d %d %d %c", &kind, &k[0], &k[1], &k[2], &k[3], &k[4], &k[5], &k[6], &val, &extra);
+    if (got == 8) { val = k[6]; k[6] = 1; }
+    else if (got != 9) return fail(SNA_E_CFG_RANGE, "tuning line not understood: %s", ln.c_str());
+    if (k[6] < 1) return fail(SNA_E_CFG_RANGE, "tuning line out of range: %s", ln.c_str());
+    const TuneKey key = {k[0], k[1], k[2], k[3], k[4], k[5], k[6]};
     if (kind == 'v' && val >= 0 && val < igemm_num_variants()) tv[key] = val;
     else if (kind == 's' && (val == 0 || val == 1)) ts[key] = val;
     else return fail(SNA_E_CFG_RANGE, "tuning line out of range: %s", ln.c_str());

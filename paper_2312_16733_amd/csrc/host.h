@@ -28,12 +28,15 @@ struct ArchTables {
 sna_status build_tables(const sna_arch_desc* arch, ArchTables* t);
 sna_status fail(sna_status st, const char* fmt, ...);
 
+// Tuning table key: (M, K_out, C_in, taps, stride, parts, same-shaped problems sharing the launch)
+typedef std::array<int, 7> TuneKey;
+
 struct ProfRec {
   int kc; hipEvent_t a, b; std::string what;
   double flops = 0, bytes = 0;       // algorithmic work of the launch
   bool igemm = false;                // a matrix-kernel launch: `key` is the tuning key of its problem with the most work
   int variant = -1;                  // the tile variant that launch ran with
-  std::array<int, 6> key{};
+  TuneKey key{};
 };
 
 struct Group {
@@ -87,9 +90,9 @@ struct sna_supernet {
   int* counters = nullptr;           // kTileCounters ints, all zero between launches (in-kernel split reductions)
   int split_mode = 0;                // 0 auto, 1 never split a reduction over blocks, 2 always when chunked
   // tile variant measured best for a layer shape: (M, K_out, C_in, R*S, stride, parts) -> variant
-  std::map<std::array<int, 6>, int> tuned;
+  std::map<sna::TuneKey, int> tuned;
   // measured for a chunked layer shape: 1 = one block per K chunk plus the reduction kernel is faster
-  std::map<std::array<int, 6>, int> tuned_split;
+  std::map<sna::TuneKey, int> tuned_split;
   // SubnetNorm calibration in progress: every layer with statistics keeps its raw output, measures it
   // and writes the subnet's row of the caller's table (stats_mut) before normalising
   bool calibrating = false;

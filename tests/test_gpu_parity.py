@@ -622,15 +622,19 @@ def test_tuning_table_round_trip_and_rejects_bad_lines(torch_mod):
         torch.cuda.synchronize()
         text = net.tuning_export()
         lines = [ln for ln in text.splitlines() if ln]
-        assert len(lines) == net.tuned_count() and all(ln[0] in "vs" and len(ln.split()) == 8 for ln in lines)
+        assert len(lines) == net.tuned_count() and all(ln[0] in "vs" and len(ln.split()) == 9 for ln in lines)
         other.tuning_import("# comment\n" + text)
         assert other.tuned_count() == net.tuned_count()
         assert sorted(other.tuning_export().splitlines()) == sorted(lines)
         a = run_single(torch, net, spec, c, x)
         b = run_single(torch, other, spec, c, x)
         np.testing.assert_array_equal(a, b)
+        # a line without the twin count (the older form) is one twin
+        other.tuning_import("v 24 24 24 1 1 1 0\n")
+        assert "v 24 24 24 1 1 1 1 0" in other.tuning_export().splitlines()
         n0 = other.tuned_count()
-        for bad in ("v 1 2 3\n", "v 64 64 64 1 1 1 999\n", "x 1 2 3 4 5 6 0\n", "s 1 2 3 4 5 0 7\n"):
+        for bad in ("v 1 2 3\n", "v 64 64 64 1 1 1 999\n", "x 1 2 3 4 5 6 0\n", "s 1 2 3 4 5 0 7\n", "v 64 64 64 1 1 1 0 0\n",
+                    "v 64 64 64 1 1 1 1 0 5\n"):
             with pytest.raises(sna.SnaError):
                 other.tuning_import(text + bad)
             assert other.tuned_count() == n0
