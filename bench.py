@@ -227,7 +227,8 @@ def main():
                    "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12 if v["ms"] > 0 else 0.0,
                    "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0}
                for k, v in prof.items()}
-    traffic, traffic_mix = stored_traffic()
+    # the counter summary was taken on the ResNet-shaped bench; the other families have none (traffic: null)
+    traffic, traffic_mix = stored_traffic() if args.family == "resnet" else (None, None)
     # the class as a whole is graded by the rule used per layer: with the workload's arithmetic intensity
     # below the ridge it is bound by HBM bandwidth, above it by the matrix pipe
     hbm_bound = ai < ridge

@@ -146,6 +146,23 @@ struct StemPoolProblem {
 };
 struct StemPoolArgs { int n; int total_tiles; StemPoolProblem p[SNA_MAX_GROUPS]; };
 
+// Head of the MBV3-shaped SuperNet in one launch: stem 3x3/2 (3 -> 16) + SubnetNorm + hardswish, depthwise 3x3 +
+// SubnetNorm + ReLU, pointwise 16 -> 16 + SubnetNorm, residual.
+struct Mbv3HeadProblem {
+  const void* x;        // request images [N][H][W][pix_e], channels 0..2 used
+  void* y;              // [N][Ho][Wo][16]
+  const void* w_stem; const void* w_dw; const void* w_pw;   // first tap / first element of the slices
+  const float *sc0, *sh0, *sc1, *sh1, *sc2, *sh2;           // folded SubnetNorm of the three layers
+  int N, H, W, Ho, Wo;
+  int pix_e;            // elements between input pixels: 3 for images read in place, 8 for the channel-padded copy
+  int wk0, wr0, ws0;    // element strides of the stored stem weights (out channel, tap row, tap column)
+  int wr1, ws1;         // depthwise kernel: tap row, tap column
+  int wk2;              // pointwise weights: out channel
+  int tiles_x, tiles_y; // 14 x 14 output tiles per image (filled by the launcher)
+  int tile_start, tiles;
+};
+struct Mbv3HeadArgs { int n; Mbv3HeadProblem p[SNA_MAX_GROUPS]; };
+
 struct CopyItem { unsigned long src, dst; unsigned long n; };   // byte offsets / length (even)
 #define SNA_COPY_ITEMS 128
 struct CopyArgs { const void* src; void* dst; int n; CopyItem it[SNA_COPY_ITEMS]; };
@@ -184,6 +201,8 @@ hipError_t launch_igemm(const ConvGroupArgs& a, int variant, bool chunked, hipSt
 bool igemm_variant_ok(int variant, const ConvProblem& p);   // can this tile variant run this problem (some take 3x3 stride-1 layers only)
 hipError_t launch_splitk_reduce(const ConvGroupArgs& a, hipStream_t s);
 hipError_t launch_stem_pool(const StemPoolArgs& a, hipStream_t s);
+hipError_t launch_mbv3_head(const Mbv3HeadArgs& a, hipStream_t s);
+int mbv3_head_channels();                          // the width launch_mbv3_head is built for
 void igemm_tile_shape(int variant, int* bm, int* bn);
 int igemm_num_variants();
 hipError_t launch_direct_conv(const ConvGroupArgs& a, int dtype, hipStream_t s);

@@ -643,6 +643,14 @@ struct Fwd {
     for (const Group& g : groups) fused = fused && g.cfg->stage_out_ch[0] <= 64;
     return fused && !net->calibrating;     // calibration needs the stem's bare output
   }
+  // MBV3 family: stem + fixed first block as one kernel (which also reads unpadded images)
+  bool mbv3_fused_head() const {
+    const sna_arch_desc& a = T().arch;
+    const sna_tensor_info& ws = tensor("stem.w");
+    const sna_tensor_info& wd = tensor("first.dw.w");
+    return a.dtype == SNA_DTYPE_BF16 && a.in_ch == 3 && a.stem_ch == mbv3_head_channels() && ws.dims[1] == 3 && ws.dims[2] == 3 &&
+           wd.dims[0] >= 3 && wd.dims[1] >= 3 && !net->calibrating;     // calibration needs every layer's bare output
+  }
   sna_status run_tiny(const void* inputs, float* logits);
   sna_status run_resnet(const void* inputs, float* logits);
   sna_status run_mbv3(const void* inputs, float* logits);
@@ -891,6 +899,48 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
   auto sn = [&](ConvProblem& p, const std::string& name, const Group& g) {
     p.scale = scale_of(name, g.cfg->subnet_id); p.shift = shift_of(name, g.cfg->subnet_id);
   };
+  if (mbv3_fused_head()) {
+    Mbv3HeadArgs ha;
+    ha.n = 0;
+    double flops = 0, bytes = 0;
+    auto flush = [&] {
+      if (ha.n) emit(PlanOp::MBV3HEAD, 0, 0, KC_STEMPOOL, flops, bytes, ha);
+      ha.n = 0; flops = 0; bytes = 0;
+    };
+    for (Group& g : groups) {
+      ConvProblem c, pw;
+      memset(&c, 0, sizeof(c));
+      c.N = g.n; c.H = g.H; c.W = g.W; c.C = g.C;
+      slice_conv(c, tensor("stem.w"), a.stem_ch, 3, 2);
+      DwProblem d;
+      memset(&d, 0, sizeof(d));
+      d.N = g.n; d.H = c.Ho; d.W = c.Wo; d.C = a.stem_ch;
+      slice_dw(d, tensor("first.dw.w"), 3, 1);
+      memset(&pw, 0, sizeof(pw));
+      pw.N = g.n; pw.H = c.Ho; pw.W = c.Wo; pw.C = a.stem_ch;
+      slice_conv(pw, tensor("first.pw.w"), a.stem_ch, 1, 1);
+      Mbv3HeadProblem p;
+      memset(&p, 0, sizeof(p));
+      p.x = g.cur; p.y = g.buf[1];
+      p.w_stem = c.w; p.wk0 = c.wk; p.wr0 = c.wr; p.ws0 = c.ws;
+      p.w_dw = d.w; p.wr1 = d.wr; p.ws1 = d.ws;
+      p.w_pw = pw.w; p.wk2 = pw.wk;
+      p.sc0 = scale_of("stem.sn", g.cfg->subnet_id); p.sh0 = shift_of("stem.sn", g.cfg->subnet_id);
+      p.sc1 = scale_of("first.sn1", g.cfg->subnet_id); p.sh1 = shift_of("first.sn1", g.cfg->subnet_id);
+      p.sc2 = scale_of("first.sn2", g.cfg->subnet_id); p.sh2 = shift_of("first.sn2", g.cfg->subnet_id);
+      p.N = g.n; p.H = g.H; p.W = g.W; p.Ho = c.Ho; p.Wo = c.Wo;
+      p.pix_e = g.raw_input ? a.in_ch : 8;
+      const double px = (double)g.n * c.Ho * c.Wo, mac = px * a.stem_ch * (9.0 * a.in_ch + 9.0 + a.stem_ch);
+      macs += (int64_t)mac;
+      flops += 2 * mac;
+      bytes += 2.0 * ((double)g.n * g.H * g.W * a.in_ch + px * a.stem_ch) +
+               2.0 * a.stem_ch * (9.0 * a.in_ch + 9.0 + a.stem_ch) + 24.0 * a.stem_ch;
+      if (ha.n == SNA_MAX_GROUPS) flush();
+      ha.p[ha.n++] = p;
+      g.cur = p.y; g.cur_buf = 1; g.H = c.Ho; g.W = c.Wo; g.C = a.stem_ch;
+    }
+    flush();
+  } else {
   conv_slot(false, [&](Group& g, ConvProblem& p) {
     p.x = g.cur; p.N = g.n; p.H = g.H; p.W = g.W; p.C = g.C;
     slice_conv(p, tensor("stem.w"), a.stem_ch, 3, 2);
@@ -916,6 +966,7 @@ sna_status Fwd::run_mbv3(const void*, float* logits) {
     g.cur = p.y; g.cur_buf = 1;
     return true;
   });
+  }
   for (int s = 0; s < a.n_stages; ++s)
     for (int j = 0; j < a.stage_max_depth[s]; ++j) {
       const std::string pre = "s" + std::to_string(s) + ".b" + std::to_string(j) + ".";
@@ -1158,6 +1209,7 @@ static hipError_t run_op(const PlanOp& op, hipStream_t s) {
     case PlanOp::COPY: return launch_copy(*(const CopyArgs*)a, s);
     case PlanOp::PAD: return launch_pad_input(*(const PadArgs*)a, s);
     case PlanOp::STEMPOOL: return launch_stem_pool(*(const StemPoolArgs*)a, s);
+    case PlanOp::MBV3HEAD: return launch_mbv3_head(*(const Mbv3HeadArgs*)a, s);
     case PlanOp::NORMCAL: return launch_norm_calibrate(*(const NormCalArgs*)a, s);
     case PlanOp::NORMAPPLY: return launch_norm_apply(*(const NormApplyArgs*)a, op.flag, s);
   }
@@ -1205,6 +1257,11 @@ static void visit_io_pointers(const PlanOp& op, F&& f) {
     case PlanOp::PAD: { const PadArgs* a = (const PadArgs*)base; at(&a->src); at(&a->dst); break; }
     case PlanOp::STEMPOOL: {
       const StemPoolArgs* a = (const StemPoolArgs*)base;
+      for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
+      break;
+    }
+    case PlanOp::MBV3HEAD: {
+      const Mbv3HeadArgs* a = (const Mbv3HeadArgs*)base;
       for (int i = 0; i < a->n; ++i) { at(&a->p[i].x); at(&a->p[i].y); }
       break;
     }
@@ -1575,7 +1632,7 @@ static sna_status forward_impl(sna_supernet* net, const sna_subnet_cfg* cfgs, in
   }
 
   if (a.family == SNA_FAMILY_RESNET || a.family == SNA_FAMILY_MBV3)
-    f.pad_inputs(inputs_dev, req_off, a.family == SNA_FAMILY_RESNET && f.resnet_fused_stem());
+    f.pad_inputs(inputs_dev, req_off, a.family == SNA_FAMILY_RESNET ? f.resnet_fused_stem() : f.mbv3_fused_head());
   else f.bind_inputs(inputs_dev, req_off, req_bytes);
   sna_status st;
   switch (a.family) {

@@ -57,7 +57,7 @@ struct Group {
 
 // One recorded kernel launch of a forward call.
 struct PlanOp {
-  enum Type { IGEMM, KREDUCE, DIRECT, MAXPOOL, GAP, DW, SE, LN, ATTN, COPY, PAD, STEMPOOL, NORMCAL, NORMAPPLY } type;
+  enum Type { IGEMM, KREDUCE, DIRECT, MAXPOOL, GAP, DW, SE, LN, ATTN, COPY, PAD, STEMPOOL, MBV3HEAD, NORMCAL, NORMAPPLY } type;
   int variant = 0, flag = 0;         // igemm: tile variant, chunked kernel; direct / pool: dtype
   int kc = 0;                        // kernel class for the per-launch timing
   double flops = 0, bytes = 0;
