@@ -86,7 +86,7 @@ def test_workspace_grows_with_batch():
 @pytest.mark.parametrize("family", ["resnet", "mbv3", "transformer"])
 def test_shipped_tuning_tables_are_well_formed(family):
     """The tables `bench.py --save-tuning` wrote: every line is a tile-variant ("v") or K-split ("s")
-    entry with 6 key fields and a value the library accepts (an import would drop anything else)."""
+    entry with 7 key fields (the last: same-shaped problems sharing the launch) and a value the library accepts (an import would drop anything else)."""
     path = os.path.join(os.path.dirname(sna.library_path()), "tuned", f"gfx950_{family}.txt")
     nv = sna.lib().sna_tile_variant_count()
     assert nv >= 7
@@ -95,10 +95,11 @@ def test_shipped_tuning_tables_are_well_formed(family):
         if line.startswith("#") or not line.strip():
             continue
         f = line.split()
-        assert f[0] in ("v", "s") and len(f) == 8, line
-        key = tuple(int(x) for x in f[1:7])
-        val = int(f[7])
-        m, k, c, taps, stride, parts = key
+        assert f[0] in ("v", "s") and len(f) == 9, line
+        key = tuple(int(x) for x in f[1:8])
+        val = int(f[8])
+        m, k, c, taps, stride, parts, twins = key
+        assert 1 <= twins <= 16, line
         assert m >= 1 and k >= 8 and k % 8 == 0 and c >= 8 and c % 8 == 0 and taps in (1, 9, 49) and stride in (1, 2, 128), line
         assert (0 <= val < nv and parts >= 1) if f[0] == "v" else (val in (0, 1) and parts == 0), line
         assert (f[0], key) not in seen, line
